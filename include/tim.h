@@ -1,0 +1,252 @@
+/*
+ * tim.h - C ABI of the working-memory decoding path for AMD MI355X (gfx950).
+ *
+ * The path is the GPU-side memory management of the paper's inference runtime
+ * (Sec. 3.1): before a decode step, the subtask lists that left the pruning
+ * buffer are evicted from the paged KV cache, their pages are recycled, the
+ * surviving tokens receive contiguous positions again (Eq. 1, here in its
+ * weight-free form: cached RoPE keys are re-rotated by their position change),
+ * and paged grouped-query decode attention runs over the retained working
+ * memory only.
+ *
+ * Conventions that hold for every call below
+ *   - Returns TIM_OK (0) or a negative tim_error.  Errors the host can see
+ *     (null pointers, shapes the kernels do not support, a HIP launch failure)
+ *     are returned at once.  Errors only the device can see (page pool
+ *     exhausted, a sequence outgrowing its page table, a malformed tree) are
+ *     written to the sticky device word tim_state.status (first error wins) and
+ *     turn the call into a no-op for the state it guards; read it with
+ *     tim_status().
+ *   - All pointers named "device" are device memory owned by the caller for the
+ *     lifetime of the context.  The library allocates no device memory and
+ *     keeps only the pointers it is given.  Pointers named "host" are ordinary
+ *     host memory read during the call.
+ *   - Every call is asynchronous on the given stream (a hipStream_t passed as
+ *     void*; NULL is the default stream), except tim_status(), which waits.
+ *     One context serves one stream at a time.
+ *   - Shapes: head_dim = 128, page_size = 16, q_heads = 4 * kv_heads.  Other
+ *     values are rejected with TIM_ERR_INVALID_ARG.
+ *   - bf16 is the upper half of an IEEE binary32, round-to-nearest-even.
+ *
+ * Data layout
+ *   K and V pools: bf16 [layers][num_pages][kv_heads][page_size][head_dim],
+ *   so the 16 rows of one (page, kv head) are 4 KiB contiguous.  Keys are
+ *   stored rotated (RoPE, pairs (i, i + 64), theta_i = rope_base^(-2i/128)) at
+ *   their current position.  A token with logical index t of sequence b lives
+ *   in page page_table[b][t / 16], row t % 16.  "slot" = page * 16 + row.
+ *
+ * Order of one decode step
+ *   tim_tree_mark (structure seen at this boundary)
+ *   [flush:  tim_prune_plan -> tim_kv_compact -> tim_plan_commit]
+ *   tim_seq_advance
+ *   per layer:  tim_kv_append, tim_decode_attn
+ */
+#ifndef TIM_H
+#define TIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tim_ctx tim_ctx;
+typedef void *tim_stream; /* hipStream_t */
+
+typedef enum {
+  TIM_OK = 0,
+  TIM_ERR_INVALID_ARG = -1,
+  TIM_ERR_BAD_TREE = -2,     /* mark or node span outside the sequence / tables */
+  TIM_ERR_OOM_PAGES = -3,    /* free stack holds fewer pages than a batch needs */
+  TIM_ERR_HIP = -4,          /* a HIP runtime call failed */
+  TIM_ERR_SEQ_TOO_LONG = -5  /* a sequence needs more than max_pages_per_seq pages */
+} tim_error;
+
+/* Structural marks of the task tree (Sec. 2.1: thought, subtasks, conclusion). */
+typedef enum {
+  TIM_MARK_OPEN = 1,      /* the task's first token comes next */
+  TIM_MARK_SUB_BEGIN = 2, /* its thought ended, its subtask list starts */
+  TIM_MARK_SUB_END = 3,   /* the list is complete: it enters the pruning buffer */
+  TIM_MARK_CLOSE = 4      /* its conclusion ended */
+} tim_mark;
+
+typedef enum { TIM_OUT_F32 = 0, TIM_OUT_BF16 = 1 } tim_out_dtype;
+
+typedef struct {
+  int32_t layers;
+  int32_t q_heads;
+  int32_t kv_heads;
+  int32_t head_dim;          /* 128 */
+  int32_t page_size;         /* 16 */
+  int32_t num_pages;         /* pages per layer in each pool */
+  int32_t max_batch;         /* sequences; all of them decode every step */
+  int32_t max_pages_per_seq; /* row length of page_table */
+  int32_t max_nodes;         /* task-tree nodes per sequence */
+  float rope_base;           /* 1e6 in the configurations */
+} tim_config;
+
+/* Caller-owned device buffers that make up one decoding context. */
+typedef struct {
+  void *k_pool;              /* device bf16, layout above */
+  void *v_pool;              /* device bf16, layout above */
+  int32_t *page_table;       /* device [max_batch][max_pages_per_seq], -1 = none */
+  int32_t *seq_len;          /* device [max_batch], tokens in the working memory */
+  int32_t *free_stack;       /* device [num_pages], free page ids, bottom first */
+  int32_t *free_top;         /* device [1], number of free pages */
+  int32_t *status;           /* device [1], sticky first device-side error */
+  /* task tree per sequence, boundaries in current logical coordinates, -1 = unset */
+  int32_t *node_tok_begin;   /* device [max_batch][max_nodes] */
+  int32_t *node_sub_begin;   /* device [max_batch][max_nodes] */
+  int32_t *node_sub_end;     /* device [max_batch][max_nodes] */
+  int32_t *node_tok_end;     /* device [max_batch][max_nodes] */
+  int32_t *node_list_order;  /* device [max_batch][max_nodes], completion ordinal of the list */
+  int32_t *n_nodes;          /* device [max_batch], 1 + highest node id marked */
+  int32_t *lists_done;       /* device [max_batch], lists completed so far */
+  float *attn_ws;            /* device scratch for split partials, see tim_attn_ws_bytes */
+  int64_t attn_ws_bytes;
+} tim_state;
+
+/*
+ * Caller-owned device scratch that carries one flush from tim_prune_plan to
+ * tim_kv_compact and tim_plan_commit.  T = max_pages_per_seq * page_size.
+ * Row e belongs to the e-th flushed sequence.  Contents are outputs of
+ * tim_prune_plan; the caller may read them back (they are the plan).
+ */
+typedef struct {
+  int32_t max_seqs;     /* capacity in sequences (host field) */
+  int32_t n_seqs;       /* set by tim_prune_plan (host field) */
+  int32_t *seq_ids;     /* device [max_seqs]   flushed sequence ids, ascending */
+  int32_t *cover;       /* device [max_seqs][T+1] scratch: pruned-range difference array */
+  int32_t *rank;        /* device [max_seqs][T+1] survivors before boundary t */
+  int32_t *kept_idx;    /* device [max_seqs][T]   old index of new token j, j < n_kept */
+  int32_t *new_pos;     /* device [max_seqs][T]   new index of old token t, -1 = pruned */
+  int32_t *delta;       /* device [max_seqs][T]   j - kept_idx[j] (<= 0) */
+  int32_t *src_slot;    /* device [max_seqs][T]   old slot of new token j, j in [keep_pages*16, n_kept) */
+  int32_t *dst_slot;    /* device [max_seqs][T]   new slot of new token j, same range */
+  int32_t *new_table;   /* device [max_seqs][max_pages_per_seq] page-table row after the flush */
+  int32_t *hdr;         /* device [max_seqs][TIM_PLAN_HDR] per-sequence scalars, see below */
+  int32_t *totals;      /* device [TIM_PLAN_TOTALS] */
+} tim_plan;
+
+enum {
+  TIM_HDR_SEQ = 0,          /* sequence id */
+  TIM_HDR_N = 1,            /* tokens before the flush */
+  TIM_HDR_N_KEPT = 2,       /* m: tokens after */
+  TIM_HDR_FIRST_PRUNED = 3, /* first pruned token (n if none) */
+  TIM_HDR_KEEP_PAGES = 4,   /* leading pages that stay in place */
+  TIM_HDR_NEED = 5,         /* fresh pages taken */
+  TIM_HDR_PAGE_OFF = 6,     /* exclusive sum of NEED over earlier sequences */
+  TIM_HDR_PUSH = 7,         /* old pages returned */
+  TIM_HDR_PUSH_OFF = 8,     /* exclusive sum of PUSH over earlier sequences */
+  TIM_HDR_BAD = 9,          /* 1 = tree rejected, sequence left untouched */
+  TIM_PLAN_HDR = 16
+};
+enum {
+  TIM_TOT_OK = 0,        /* 1 = plan valid; 0 = pool exhausted, flush is a no-op */
+  TIM_TOT_NEED = 1,
+  TIM_TOT_PUSH = 2,
+  TIM_TOT_TOP_AFTER_POP = 3,
+  TIM_TOT_TOP_BEFORE = 4,
+  TIM_PLAN_TOTALS = 8
+};
+
+/* Bytes of tim_state.attn_ws that tim_decode_attn needs for this configuration. */
+int64_t tim_attn_ws_bytes(const tim_config *cfg);
+
+/* Creates a context (host object only).  cfg is copied.  Shapes are checked. */
+int tim_ctx_create(tim_ctx **out, const tim_config *cfg);
+int tim_ctx_destroy(tim_ctx *ctx);
+
+/* Attaches the caller's device buffers; all pointers must be non-null. */
+int tim_bind(tim_ctx *ctx, const tim_state *state);
+
+/*
+ * Empties the context: free_stack[i] = num_pages-1-i (so the first pops hand out
+ * pages 0, 1, 2, ...), free_top = num_pages, all sequences empty, page tables and
+ * trees unset, status cleared.  The paper recycles pages of pruned tokens
+ * (Sec. 1, Sec. 3.1) without fixing an order; the LIFO order here is this
+ * library's, chosen so page tables are reproducible.
+ */
+int tim_pool_reset(tim_ctx *ctx, tim_stream stream);
+
+/*
+ * Structure tracking (Sec. 2.1, Sec. 3.1: the runtime follows the structure of
+ * the reasoning while it is generated).  ops: device int32 [n_ops][4] =
+ * (sequence, tim_mark, node id, boundary).  boundary = -1 stands for the
+ * sequence's current length (the mark sits right before the pending token);
+ * an explicit boundary serves bulk loading.  Ops of one sequence are applied in
+ * array order.  TIM_MARK_SUB_END also stamps the node's list with the next
+ * completion ordinal of its sequence.  Bad ids set TIM_ERR_BAD_TREE and are skipped.
+ */
+int tim_tree_mark(tim_ctx *ctx, const int32_t *ops, int32_t n_ops, tim_stream stream);
+
+/*
+ * Reserves the slot of each sequence's pending token: a sequence whose length is
+ * a multiple of 16 pops one page (sequences served in ascending id), then every
+ * length grows by one.  If the pool cannot serve the whole batch, or a page
+ * table is full, nothing changes and status is set.
+ */
+int tim_seq_advance(tim_ctx *ctx, tim_stream stream);
+
+/*
+ * Writes the pending token's key and value of one layer into slot seq_len-1 of
+ * every sequence.  k_new, v_new: device bf16 [max_batch][kv_heads][128]; the key
+ * is already rotated at position seq_len-1.
+ */
+int tim_kv_append(tim_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, tim_stream stream);
+
+/*
+ * The pruning rule and the plan that follows from it (Sec. 2.1 "Subtask
+ * pruning", Sec. 3.1).  For each listed sequence every subtask list that has
+ * left the pruning buffer - all completed lists but the `threshold` most recent
+ * ones, i.e. the first-in-first-out buffer of the paper - loses the tokens
+ * between its task's thought and conclusion.  Survivors keep their order and
+ * get positions 0..m-1.  Pages that lie wholly before the first pruned token
+ * stay; the rest of the survivors is planned into fresh pages popped here
+ * (ascending sequence, ascending page); if only a tail is pruned nothing moves.
+ * seq_ids: device int32 [n_seqs], strictly ascending.  If the pool cannot supply
+ * all fresh pages the plan is marked invalid, status is set and the three flush
+ * calls change nothing.
+ */
+int tim_prune_plan(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t threshold, tim_plan *plan,
+                   tim_stream stream);
+
+/*
+ * Moves the planned survivors of layers [layer_begin, layer_end): values are
+ * copied bit for bit; a key with position change d != 0 is rotated by d (the
+ * RoPE composition R(p+d) = R(d) R(p) applied to the stored key: the positional
+ * part of Eq. 1), in fp32 with angles reduced in fp64, and rounded to bf16; a key
+ * with d = 0 is copied bit for bit.  Source and destination pages are disjoint.
+ */
+int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_begin, int32_t layer_end, tim_stream stream);
+
+/*
+ * Completes the flush: returns the replaced pages to the free stack (ascending
+ * sequence, ascending logical page), installs the new page-table rows and
+ * lengths, and moves every node boundary b of the flushed sequences to rank[b].
+ */
+int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream stream);
+
+/*
+ * Paged grouped-query decode attention of one layer over each sequence's whole
+ * working memory (Sec. 3.1: paged attention over the pruned cache): for query
+ * head h and its KV head h/4, out = softmax(sm_scale * q K^T) V over tokens
+ * 0..seq_len-1, bf16 inputs, fp32 accumulation.  q: device bf16
+ * [max_batch][q_heads][128], rotated at position seq_len-1.  out: device
+ * [max_batch][q_heads][128] in out_dtype.  max_seq_len: an upper bound on the
+ * batch's lengths used only to size the launch (0 = assume full tables); longer
+ * sequences are still handled in full.  Uses tim_state.attn_ws.
+ */
+int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
+                    int32_t max_seq_len, tim_stream stream);
+
+/* out: device int32 [2] = (free pages, pages referenced by page tables). */
+int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream);
+
+/* Waits for the stream, returns the sticky device status and clears it. */
+int tim_status(tim_ctx *ctx, tim_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIM_H */

@@ -1,0 +1,142 @@
+// KV compaction with RoPE re-rotation: gathers the planned survivors into their fresh
+// pages.  HBM-bound: 4096 B read + 4096 B written per moved token per layer.
+//
+// Mapping.  One block of 128 threads owns one destination page (16 tokens) for a group
+// of layers and all KV heads.  Thread (t, c) = (tid / 8, tid % 8) owns token t and the
+// eight rotation pairs (8c+k, 64+8c+k): two 16-byte pieces of the K row, 128 B apart, and
+// the same two pieces of the V row.  Eight neighbouring threads cover 128 contiguous
+// bytes, so every access is a full line of a 256-byte row; rows of one source run are
+// adjacent in memory.  The cos/sin of the token's position change are computed once per
+// thread (angle in fp64, reduced to [-pi, pi], then fp32 sincos) and reused for every
+// head and layer of the group, which keeps the kernel on the bandwidth roof.
+#include "tim_internal.h"
+
+#define CP_THREADS 128
+#define CP_LAYERS_PER_BLOCK 4
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// two floats -> packed bf16 pair, round to nearest even (hardware conversion on gfx950)
+__device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
+  float2_t f = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return __builtin_bit_cast(uint32_t, b);
+}
+
+__global__ void __launch_bounds__(CP_THREADS)
+tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int layer_begin, int layer_end, double theta1,
+                   double theta8) {
+  const int e = blockIdx.y;
+  if (!pl.totals[TIM_TOT_OK]) return;
+  const int32_t *hdr = pl.hdr + (int64_t)e * TIM_PLAN_HDR;
+  if (hdr[TIM_HDR_BAD]) return;
+  const int m = hdr[TIM_HDR_N_KEPT], keep = hdr[TIM_HDR_KEEP_PAGES];
+  const int p = keep + blockIdx.x;
+  if (p * TIM_PS >= m) return;
+  const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
+  const int j = p * TIM_PS + t;
+  if (j >= m) return;  // ragged last page; no block-wide sync below
+  const int T = cfg.max_pages_per_seq * TIM_PS;
+  const int src = pl.src_slot[(int64_t)e * T + j];
+  const int dst = pl.dst_slot[(int64_t)e * T + j];
+  const int d = pl.delta[(int64_t)e * T + j];
+  const int64_t nslots = (int64_t)cfg.num_pages * TIM_PS;
+  if (src < 0 || src >= nslots || dst < 0 || dst >= nslots) {
+    tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+    return;
+  }
+
+  float cs[8], sn[8];
+  if (d != 0) {
+    double th = 1.0;
+    for (int q = 0; q < c; ++q) th *= theta8;  // theta_{8c}
+    const double two_pi_hi = 6.283185307179586232e+00, two_pi_lo = 2.449293598294706414e-16;
+    const double inv_two_pi = 1.591549430918953456e-01;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const double a = (double)d * th;
+      const double n2 = rint(a * inv_two_pi);
+      double r = fma(-n2, two_pi_hi, a);
+      r = fma(-n2, two_pi_lo, r);
+      sincosf((float)r, &sn[k], &cs[k]);
+      th *= theta1;
+    }
+  }
+
+  const int l0 = layer_begin + blockIdx.z * CP_LAYERS_PER_BLOCK;
+  const int l1 = min(l0 + CP_LAYERS_PER_BLOCK, layer_end);
+  const uint4 *kp = reinterpret_cast<const uint4 *>(st.k_pool);
+  const uint4 *vp = reinterpret_cast<const uint4 *>(st.v_pool);
+  uint4 *kw = reinterpret_cast<uint4 *>(st.k_pool);
+  uint4 *vw = reinterpret_cast<uint4 *>(st.v_pool);
+  const int hkv = cfg.kv_heads;
+  // offsets in uint4 (16 B) units: tile = 256 units, row = 16 units
+  const int64_t s_off = (int64_t)(src / TIM_PS) * hkv * 256 + (src % TIM_PS) * 16 + c;
+  const int64_t d_off = (int64_t)(dst / TIM_PS) * hkv * 256 + (dst % TIM_PS) * 16 + c;
+  for (int layer = l0; layer < l1; ++layer) {
+    const int64_t lbase = (int64_t)layer * cfg.num_pages * hkv * 256;
+    // heads go two at a time with all eight loads issued before the first store: source
+    // and destination live in the same pool, so the compiler may not reorder them itself
+    for (int h = 0; h < hkv; h += 2) {
+      const bool two = h + 1 < hkv;
+      const int64_t so = lbase + s_off + (int64_t)h * 256;
+      const int64_t dof = lbase + d_off + (int64_t)h * 256;
+      uint4 klo[2], khi[2], vlo[2], vhi[2];
+      klo[0] = kp[so];
+      khi[0] = kp[so + 8];
+      vlo[0] = vp[so];
+      vhi[0] = vp[so + 8];
+      if (two) {
+        klo[1] = kp[so + 256];
+        khi[1] = kp[so + 256 + 8];
+        vlo[1] = vp[so + 256];
+        vhi[1] = vp[so + 256 + 8];
+      }
+      if (d != 0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          uint32_t *a = reinterpret_cast<uint32_t *>(&klo[u]);
+          uint32_t *b = reinterpret_cast<uint32_t *>(&khi[u]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float x0 = bf_lo(a[w]), x1 = bf_hi(a[w]);  // dims 8c+2w, 8c+2w+1
+            const float y0 = bf_lo(b[w]), y1 = bf_hi(b[w]);  // their partners at +64
+            const float c0 = cs[2 * w], s0 = sn[2 * w], c1 = cs[2 * w + 1], s1 = sn[2 * w + 1];
+            const float rx0 = fmaf(x0, c0, -(y0 * s0)), ry0 = fmaf(y0, c0, x0 * s0);
+            const float rx1 = fmaf(x1, c1, -(y1 * s1)), ry1 = fmaf(y1, c1, x1 * s1);
+            a[w] = bf_pack(rx0, rx1);
+            b[w] = bf_pack(ry0, ry1);
+          }
+        }
+      }
+      kw[dof] = klo[0];
+      kw[dof + 8] = khi[0];
+      vw[dof] = vlo[0];
+      vw[dof + 8] = vhi[0];
+      if (two) {
+        kw[dof + 256] = klo[1];
+        kw[dof + 256 + 8] = khi[1];
+        vw[dof + 256] = vlo[1];
+        vw[dof + 256 + 8] = vhi[1];
+      }
+    }
+  }
+}
+
+extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_begin, int32_t layer_end,
+                              tim_stream stream) {
+  if (!ctx || !ctx->bound || !plan || !plan->hdr || !plan->totals || !plan->src_slot || !plan->dst_slot ||
+      !plan->delta || plan->n_seqs <= 0 || plan->n_seqs > plan->max_seqs || layer_begin < 0 ||
+      layer_end > ctx->cfg.layers || layer_begin > layer_end)
+    return TIM_ERR_INVALID_ARG;
+  if (layer_begin == layer_end) return TIM_OK;
+  const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
+  dim3 grid(ctx->cfg.max_pages_per_seq, plan->n_seqs, groups);
+  hipLaunchKernelGGL(tim_compact_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
+                     layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
+  TIM_LAUNCH_CHECK();
+  return TIM_OK;
+}

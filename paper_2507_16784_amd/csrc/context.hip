@@ -1,0 +1,46 @@
+// Context object: configuration, the caller's buffer pointers, host-side constants.
+#include <cmath>
+#include <new>
+
+#include "tim_internal.h"
+
+extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
+  if (!out || !cfg) return TIM_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->head_dim != TIM_D || cfg->page_size != TIM_PS || cfg->kv_heads <= 0 ||
+      cfg->q_heads != TIM_G * cfg->kv_heads || cfg->layers <= 0 || cfg->num_pages <= 0 || cfg->max_batch <= 0 ||
+      cfg->max_pages_per_seq <= 0 || cfg->max_nodes <= 0 || !(cfg->rope_base > 1.0f))
+    return TIM_ERR_INVALID_ARG;
+  // slots are int32: page * 16 + row must not overflow
+  if ((int64_t)cfg->num_pages * TIM_PS > INT32_MAX || (int64_t)cfg->max_pages_per_seq * TIM_PS > INT32_MAX / 2)
+    return TIM_ERR_INVALID_ARG;
+  tim_ctx *c = new (std::nothrow) tim_ctx();
+  if (!c) return TIM_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  c->bound = false;
+  c->n_cu = 256;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+    c->n_cu = prop.multiProcessorCount;
+  for (int i = 0; i < TIM_D / 2; ++i) c->inv_freq[i] = std::pow((double)cfg->rope_base, -2.0 * i / TIM_D);
+  *out = c;
+  return TIM_OK;
+}
+
+extern "C" int tim_ctx_destroy(tim_ctx *ctx) {
+  delete ctx;
+  return TIM_OK;
+}
+
+extern "C" int tim_bind(tim_ctx *ctx, const tim_state *s) {
+  if (!ctx || !s) return TIM_ERR_INVALID_ARG;
+  if (!s->k_pool || !s->v_pool || !s->page_table || !s->seq_len || !s->free_stack || !s->free_top || !s->status ||
+      !s->node_tok_begin || !s->node_sub_begin || !s->node_sub_end || !s->node_tok_end || !s->node_list_order ||
+      !s->n_nodes || !s->lists_done || !s->attn_ws)
+    return TIM_ERR_INVALID_ARG;
+  if (s->attn_ws_bytes < tim_attn_ws_bytes(&ctx->cfg)) return TIM_ERR_INVALID_ARG;
+  ctx->st = *s;
+  ctx->bound = true;
+  return TIM_OK;
+}

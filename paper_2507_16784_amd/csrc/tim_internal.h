@@ -1,0 +1,68 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tim.h"
+
+#define TIM_D 128          // head dim
+#define TIM_PS 16          // tokens per page
+#define TIM_G 4            // query heads per KV head
+#define TIM_ROW_BYTES 256  // one bf16 row of TIM_D
+#define TIM_TILE_BYTES (TIM_PS * TIM_ROW_BYTES)  // one (page, kv head) tile: 4 KiB
+
+struct tim_ctx {
+  tim_config cfg;
+  tim_state st;
+  bool bound;
+  int n_cu;
+  double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
+};
+
+struct RopeFreq {
+  double f[TIM_D / 2];
+};
+
+#define TIM_HIP_CHECK(expr)                  \
+  do {                                       \
+    hipError_t _e = (expr);                  \
+    if (_e != hipSuccess) return TIM_ERR_HIP; \
+  } while (0)
+
+#define TIM_LAUNCH_CHECK() TIM_HIP_CHECK(hipGetLastError())
+
+static inline hipStream_t tim_hs(tim_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+__device__ __forceinline__ void tim_set_status(int32_t *status, int32_t err) { atomicCAS(status, 0, err); }
+
+// ---- wave / block scans (wave64) -------------------------------------------------
+__device__ __forceinline__ int tim_wave_incl_scan(int v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Inclusive block scan of one int per thread; blockDim.x <= 1024, multiple of 64.
+// `smem` holds at least 17 ints.  Returns the inclusive prefix; *total = block sum.
+__device__ __forceinline__ int tim_block_incl_scan(int v, int *smem, int *total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int incl = tim_wave_incl_scan(v);
+  __syncthreads();  // protect smem reuse across calls
+  if (lane == 63) smem[w] = incl;
+  __syncthreads();
+  if (w == 0) {
+    int t = lane < nw ? smem[lane] : 0;
+    int ti = tim_wave_incl_scan(t);
+    if (lane < nw) smem[lane] = ti - t;  // exclusive wave offsets
+    if (lane == nw - 1) smem[16] = ti;
+  }
+  __syncthreads();
+  incl += smem[w];
+  *total = smem[16];
+  return incl;
+}

@@ -17,7 +17,7 @@ def make_config(wl, layers, q_heads, kv_heads, headroom_pages, max_nodes=None, h
     used = sum((p0 + page_size - 1) // page_size for p0 in wl.preload)
     return Config(layers=layers, q_heads=q_heads, kv_heads=kv_heads, head_dim=head_dim,
                   page_size=page_size, num_pages=used + headroom_pages, max_batch=b,
-                  max_pages_per_seq=mp, max_nodes=max_nodes or max(t.n_nodes for t in wl.traces),
+                  max_pages_per_seq=mp, max_nodes=max_nodes or max(1, max(t.n_nodes for t in wl.traces)),
                   rope_base=rope_base)
 
 
@@ -68,7 +68,7 @@ def step_inputs(seed, step, cfg, scale):
     return q, k, v
 
 
-def run_step(rt, wl, step, seed, scale, sm_scale, attend=True, on_event=None):
+def run_step(rt, wl, step, seed, scale, sm_scale, attend=True, on_event=None, before_event=None):
     """One decode step in the library's call order.  Returns attention outputs
     [L] of float32 [B,Hq,D] (or None)."""
     ops = wl.step_ops(step)
@@ -76,6 +76,8 @@ def run_step(rt, wl, step, seed, scale, sm_scale, attend=True, on_event=None):
         rt.mark(ops)
     seqs = wl.flush_seqs(step)
     if seqs:
+        if before_event:
+            before_event(step, seqs)
         ev = rt.prune_plan(seqs)
         rt.kv_compact(ev, 0, rt.cfg.layers)
         rt.commit(ev)

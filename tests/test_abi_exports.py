@@ -1,0 +1,45 @@
+"""The C-ABI library loads without a GPU and exports every function include/tim.h declares."""
+import ctypes
+import os
+import re
+
+from paper_2507_16784_amd import tim
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "tim.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(tim_[a-z_]+)\s*\(", src)))
+
+
+def test_header_and_binding_agree():
+    assert _declared() == sorted(tim.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(tim.LIB_PATH):
+        from paper_2507_16784_amd import build
+        build.build()
+    lib = ctypes.CDLL(tim.LIB_PATH)
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    lib = tim.lib()
+    h = ctypes.c_void_p()
+    bad = tim.tim_config(1, 8, 2, 64, 16, 8, 1, 4, 4, 1.0e6)          # head_dim 64 is unsupported
+    assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(bad)) == tim.ERR_INVALID_ARG
+    bad = tim.tim_config(1, 6, 2, 128, 16, 8, 1, 4, 4, 1.0e6)         # group size 3 is unsupported
+    assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(bad)) == tim.ERR_INVALID_ARG
+    ok = tim.tim_config(1, 8, 2, 128, 16, 8, 1, 4, 4, 1.0e6)
+    assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(ok)) == tim.OK
+    # unbound context: every stream call is refused before anything is launched
+    assert lib.tim_seq_advance(h, None) == tim.ERR_INVALID_ARG
+    assert lib.tim_pool_reset(h, None) == tim.ERR_INVALID_ARG
+    empty = tim.tim_state()
+    assert lib.tim_bind(h, ctypes.byref(empty)) == tim.ERR_INVALID_ARG
+    assert lib.tim_attn_ws_bytes(ctypes.byref(ok)) == 1 * 8 * 128 * 130 * 4
+    assert lib.tim_ctx_destroy(h) == tim.OK

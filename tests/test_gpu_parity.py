@@ -1,0 +1,311 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: every integer output bit-exact (kept lists, position maps, deltas, ranks, page
+plans, page tables, free stack, lengths, node coordinates); values and keys with zero
+position change bit-exact; re-rotated keys >= 99 % identical to the oracle's float64
+result and otherwise within one bf16 step of it, plus 2^-20 of the rotated pair's
+norm (the fp32 rotation's own error, visible only where the pair cancels to ~0); attention within 2e-2 abs + 1e-2 rel of the
+oracle, plus the sharper normalized gate max|err| <= 1e-2 * max|ref|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import harness
+from oracle import bf16
+from oracle.rope import rotate
+from oracle.runtime import OracleRuntime
+from paper_2507_16784_amd.workload.schedule import Workload, every
+from paper_2507_16784_amd.workload.tree import TreeSpec, generate
+
+pytestmark = pytest.mark.gpu
+
+SPEC_C1 = TreeSpec(depth_max=4, branch=(1, 4), thought=(16, 128), concl=(8, 32))
+SPEC_C2 = TreeSpec(depth_max=6, branch=(2, 5), thought=(32, 512), concl=(16, 64))
+SPEC_C4 = TreeSpec(depth_max=10, branch=(2, 3), thought=(16, 64), concl=(8, 16))
+SPEC_TINY = TreeSpec(depth_max=4, branch=(1, 3), thought=(2, 9), concl=(1, 4), prompt_len=5)
+
+
+@pytest.fixture(scope="module")
+def gb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_backend
+    return gpu_backend
+
+
+def bf16_steps(a, b):
+    """Distance in representable bf16 values between two bit patterns (same-sign aware)."""
+    def key(x):
+        x = x.astype(np.int32)
+        return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
+    return np.abs(key(a) - key(b))
+
+
+def check_attention(got, want):
+    err = np.abs(got - want)
+    assert np.all(err <= 2e-2 + 1e-2 * np.abs(want)), float(err.max())
+    assert err.max() <= 1e-2 * np.abs(want).max(), (float(err.max()), float(np.abs(want).max()))
+
+
+def check_plan(ev, view):
+    assert view.ok == ev.ok
+    if not ev.ok:
+        return
+    for e, sp in enumerate(ev.seqs):
+        pl = sp.plan
+        n, m = sp.n, pl.n_kept
+        h = view.hdr[e]
+        assert (h[0], h[1], h[2], h[3], h[4], h[5], h[7]) == (sp.seq, n, m, pl.first_pruned, sp.keep_pages, sp.need,
+                                                              len(sp.old_pages))
+        assert np.array_equal(view.rank[e, : n + 1], pl.rank)
+        assert np.array_equal(view.kept_idx[e, :m], pl.kept_idx)
+        assert np.array_equal(view.new_pos[e, :n], pl.new_pos)
+        assert np.array_equal(view.delta[e, :m], pl.delta)
+        assert np.array_equal(view.new_table[e], sp.new_table)
+        lo = sp.moved_begin
+        assert np.array_equal(view.src_slot[e, lo:m], sp.src_slot)
+        assert np.array_equal(view.dst_slot[e, lo:m], sp.dst_slot)
+
+
+def check_state(ora, gpu):
+    st = gpu.state()
+    assert np.array_equal(st["seq_len"], ora.seq_len)
+    assert np.array_equal(st["page_table"], ora.page_table)
+    assert st["top"] == ora.free.top and np.array_equal(st["free_ids"], ora.free.free_ids())
+    for name in ("tok_begin", "sub_begin", "sub_end", "tok_end", "list_order"):
+        assert np.array_equal(st[name], getattr(ora, name)), name
+    assert np.array_equal(st["n_nodes"], ora.n_nodes) and np.array_equal(st["lists_done"], ora.lists_done)
+    assert st["top"] + ora.pages_in_use() == ora.cfg.num_pages          # conservation on the GPU state
+    stats = gpu.ctx.tim_pool_stats().cpu().numpy()
+    assert stats[0] == st["top"] and stats[0] + stats[1] == ora.cfg.num_pages
+
+
+def check_rotated(kg, ko):
+    """Re-rotated keys against the oracle's float64 result from the same stored input."""
+    steps = bf16_steps(kg, ko)
+    if steps.max(initial=0) > 0:
+        fo, fg = bf16.to_f64(ko), bf16.to_f64(kg)
+        norm = np.hypot(fo[..., :64], fo[..., 64:])
+        norm = np.concatenate([norm, norm], axis=-1)
+        one_step = np.maximum(np.abs(fo), 2.0 ** -126) * 2.0 ** -7
+        assert np.all(np.abs(fg - fo) <= one_step + 2.0 ** -20 * norm)
+    return steps.size, int((steps == 0).sum())
+
+
+def check_event_kv(ora, gpu, ev, before):
+    """One flush, judged on the GPU's own pre-flush cache: values and unmoved keys are bit
+    copies of the survivors, moved keys equal the oracle's rotation of the same stored bits."""
+    c = ora.cfg
+    tot = same = 0
+    for sp in ev.seqs:
+        pl = sp.plan
+        for layer in range(c.layers):
+            kb, vb = before[(layer, sp.seq)]
+            kg, vg = gpu.gather_kv(layer, sp.seq)
+            assert np.array_equal(vg, vb[pl.kept_idx])
+            still = pl.delta == 0
+            assert np.array_equal(kg[still], kb[pl.kept_idx[still]])
+            want = bf16.from_f64(rotate(bf16.to_f64(kb[pl.kept_idx]), pl.delta[:, None], c.rope_base))
+            want[still] = kb[pl.kept_idx[still]]
+            n, k = check_rotated(kg, want)
+            tot += n
+            same += k
+    assert same >= 0.99 * tot
+
+
+def check_kv(ora, gpu, drift_ok=False):
+    """Whole working memory of every (layer, sequence), read through the page tables.  After
+    several flushes the two caches may have rounded a key differently once and then rotated
+    it again, so `drift_ok` only bounds that drift; a single flush is held to check_rotated."""
+    c = ora.cfg
+    tot = same = 0
+    for layer in range(c.layers):
+        for b in range(c.max_batch):
+            ko, vo = ora.gather_kv(layer, b)
+            kg, vg = gpu.gather_kv(layer, b)
+            assert np.array_equal(vg, vo)                               # values: bit copies
+            if drift_ok:
+                fo, fg = bf16.to_f64(ko), bf16.to_f64(kg)
+                norm = np.hypot(fo[..., :64], fo[..., 64:])
+                norm = np.concatenate([norm, norm], axis=-1)
+                assert np.all(np.abs(fg - fo) <= 2.0 ** -6 * norm + 1e-30)
+                st = bf16_steps(kg, ko)
+                tot += st.size
+                same += int((st == 0).sum())
+            else:
+                n, k = check_rotated(kg, ko)
+                tot += n
+                same += k
+    assert same >= 0.99 * tot
+
+
+def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1):
+    ora = OracleRuntime(cfg, threshold)
+    harness.preload_oracle(ora, wl, seed, kv_scale)
+    gpu = gb.GpuRuntime(cfg, threshold)
+    gb.preload_gpu(gpu, wl, seed, kv_scale)
+    check_state(ora, gpu)
+    check_kv(ora, gpu)
+    n_events = 0
+    for step in range(wl.steps):
+        events, views, before = [], [], {}
+        do_att = step % attend_every == 0 or step == wl.steps - 1
+        check_now = bool(wl.flush_seqs(step)) and n_events % kv_check_every == 0
+
+        def snapshot(_step, seqs):
+            if check_now:
+                for b in seqs:
+                    for layer in range(cfg.layers):
+                        before[(layer, b)] = gpu.gather_kv(layer, b)
+
+        want = harness.run_step(ora, wl, step, seed, kv_scale, sm_scale, attend=do_att,
+                                on_event=lambda s, ev: events.append(ev))
+        def after_commit(_step, _plan):
+            views.append(gpu.plan_view())
+            if check_now:                       # right after the commit, before the next token lands
+                check_event_kv(ora, gpu, events[len(views) - 1], before)
+
+        got = harness.run_step(gpu, wl, step, seed, kv_scale, sm_scale, attend=do_att, before_event=snapshot,
+                               on_event=after_commit)
+        assert gpu.status() == ora.status == 0
+        for ev, view in zip(events, views):
+            check_plan(ev, view)
+            n_events += 1
+        check_state(ora, gpu)
+        if do_att:
+            for a, b in zip(got, want):
+                check_attention(a, b)
+    check_kv(ora, gpu, drift_ok=n_events > 1)
+    return ora, gpu
+
+
+@pytest.mark.parametrize("threshold", [0, 1, 2])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config1_tiny_tree_one_flush(gb, threshold, seed):
+    """Config 1: batch 1, 1 layer, 8/2 heads, 4096-token tree, one flush, then decode."""
+    p0, steps = 4096, 3
+    wl = Workload([generate(seed, p0 + steps + 1, SPEC_C1)], [p0], steps, {0: [0]})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=300)
+    ora, _ = replay(gb, wl, cfg, threshold, seed, 128 ** -0.5, 128 ** -0.5)
+    assert ora.seq_len[0] < p0 + steps                                  # something was pruned
+
+
+@pytest.mark.parametrize("threshold,cadence", [(0, 1), (1, 3), (2, 7)])
+def test_many_small_events_multi_layer_batch(gb, threshold, cadence):
+    """Batch of 3 sequences, 2 layers, frequent flushes on small trees (ragged pages everywhere)."""
+    seeds = [11, 12, 13]
+    p0s, steps = [37, 64, 150], 120
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(cadence, steps, 3))
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=40)
+    replay(gb, wl, cfg, threshold, 5, 1.0, 128 ** -0.5)
+
+
+def test_config2_long_single_sequence(gb):
+    """Config 2 shape: 32/8 heads, a 32,768-position tree, 64 steps, flush every 8 (sharp inputs)."""
+    p0, steps = 32768 - 64, 64
+    wl = Workload([generate(3, p0 + steps + 1, SPEC_C2)], [p0], steps, every(8, steps, 1))
+    cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=2100)
+    ora, _ = replay(gb, wl, cfg, 1, 3, 1.0, 128 ** -0.5, attend_every=8, kv_check_every=4)
+    assert ora.seq_len[0] < 0.6 * (p0 + steps)
+
+
+def test_config4_prune_heavy_recycling(gb):
+    """Config 4 shape at reduced batch: deep narrow trees, flush every 2 steps, 25 % page headroom,
+    so pages are recycled through the free stack and position changes grow large."""
+    seeds = [21, 22, 23, 24]
+    p0, steps = 8192 - 96, 96
+    traces = [generate(s, p0 + steps + 1, SPEC_C4) for s in seeds]
+    wl = Workload(traces, [p0] * 4, steps, every(2, steps, 4))
+    used = 4 * ((p0 + 15) // 16)
+    cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=used // 4)
+    ora, _ = replay(gb, wl, cfg, 2, 9, 1.0, 128 ** -0.5, attend_every=16, kv_check_every=8)
+    assert ora.seq_len.max() < p0
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 255, 256, 257, 1031])
+def test_attention_lengths_and_needle(gb, n):
+    """No tree at all: plain paged decode attention at page-aligned and ragged lengths,
+    scaled and sharp inputs, fp32 and bf16 outputs, with a planted needle."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    tr = Trace(n + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr], [n, max(1, n // 2)], 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=4)
+    for kv_scale in (128 ** -0.5, 1.0):
+        ora = OracleRuntime(cfg, 0)
+        harness.preload_oracle(ora, wl, n, kv_scale)
+        gpu = gb.GpuRuntime(cfg, 0)
+        gb.preload_gpu(gpu, wl, n, kv_scale)
+        want = harness.run_step(ora, wl, 0, n, kv_scale, 128 ** -0.5)
+        got = harness.run_step(gpu, wl, 0, n, kv_scale, 128 ** -0.5)
+        check_attention(got[0], want[0])
+        # needle: make one stored key of sequence 0 align with query head 5
+        q, _, _ = harness.step_inputs(n, 0, cfg, kv_scale)
+        from oracle import bf16
+        kb, vb = ora.gather_kv(0, 0)
+        t = (n * 7) // 11
+        needle = bf16.from_f64(bf16.to_f64(q[0][0, 5]) * 40.0 / max(kv_scale, 0.2))
+        s = ora.slots_of(0, [t])[0]
+        ora.k[0, s, 1] = needle
+        kfull, vfull = ora.gather_kv(0, 0)
+        gpu.load_kv(0, 0, kfull, vfull)
+        want = ora.decode_attn(0, q[0], 1.0)
+        got = gpu.decode_attn(0, q[0], 1.0)
+        check_attention(got, want)
+        assert np.allclose(got[0, 5], bf16.to_f64(vfull[t, 1]), atol=2e-2)
+        got16 = gpu.decode_attn(0, q[0], 1.0, out_dtype=torch.bfloat16)
+        assert np.all(np.abs(got16 - want) <= 2e-2 + 1e-2 * np.abs(want))
+        assert gpu.status() == 0
+
+
+def test_pool_exhaustion_and_full_table_are_atomic(gb):
+    from paper_2507_16784_amd import tim
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    tr = Trace(200, [], [], [], [], [], [], [])
+    wl = Workload([tr], [50], 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=0, max_nodes=4)
+    for rt in (OracleRuntime(cfg, 0),):
+        pass
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 1, 1.0)
+    gb.preload_gpu(gpu, wl, 1, 1.0)
+    ops = [(0, MARK_OPEN, 0, 0), (0, MARK_SUB_BEGIN, 0, 2), (0, MARK_SUB_END, 0, 12)]
+    ora.mark(ops); gpu.mark(ops)
+    before = gpu.state()
+    ev = ora.prune_plan([0]); ora.kv_compact(ev, 0, 1); ora.commit(ev)
+    pl = gpu.prune_plan([0]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    assert not ev.ok and not gpu.plan_view().ok
+    assert gpu.status() == tim.ERR_OOM_PAGES == ora.status
+    after = gpu.state()
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k
+    check_state(ora, gpu)
+    # a sequence that fills its page table cannot advance, and nothing changes
+    wl2 = Workload([tr], [64], 1, {})
+    cfg2 = harness.make_config(wl2, layers=1, q_heads=8, kv_heads=2, headroom_pages=8, max_nodes=4,
+                               max_pages_per_seq=4)
+    ora2 = OracleRuntime(cfg2, 0); gpu2 = gb.GpuRuntime(cfg2, 0)
+    harness.preload_oracle(ora2, wl2, 1, 1.0); gb.preload_gpu(gpu2, wl2, 1, 1.0)
+    ora2.advance(); gpu2.advance()
+    assert gpu2.status() == tim.ERR_SEQ_TOO_LONG == ora2.status
+    check_state(ora2, gpu2)
+
+
+def test_reset_then_decode_from_empty(gb):
+    """tim_pool_reset order (first pops hand out 0, 1, 2, ...) and growth from an empty context."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    tr = Trace(100, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr, tr], [0, 0, 0], 40, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=12)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    check_state(ora, gpu)
+    for step in range(40):
+        want = harness.run_step(ora, wl, step, 2, 1.0, 0.1)
+        got = harness.run_step(gpu, wl, step, 2, 1.0, 0.1)
+        check_attention(got[0], want[0])
+    check_state(ora, gpu)
+    check_kv(ora, gpu)
+    assert list(ora.page_table[0, :3]) == [0, 3, 6]
