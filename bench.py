@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the working-memory decoding hot path on one MI355X.
+
+A step is one pass of the whole path over the batch: structure marks, the flushes due at
+this step (prune plan -> KV compaction with RoPE re-rotation -> commit), slot reservation,
+then per layer KV append + paged GQA decode attention.  The workload is configuration 3
+(batch 64, 36 layers, 32/8 heads, trees of 16K-32K positions, ~90 % pruned by each
+sequence's big flush), synthetic and seeded, resident in HBM before the clock starts.
+
+Prints ONE JSON line; see the design doc for the definition of every field.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "decode steps/s + achieved HBM GB/s for prune+compact+paged GQA decode attn"
+HBM_PEAK_GBPS = 8000.0
+KV_BYTES_PER_TOKEN_LAYER = 4096          # K + V rows of 8 KV heads x 128 dims, bf16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed):
+    import numpy as np
+    from paper_2507_16784_amd.workload.state import scattered_pages
+
+    B = len(wl.traces)
+    longest = max(p + wl.steps for p in wl.preload)
+    mp = (longest + 15) // 16 + 1
+    used = sum((p + 15) // 16 for p in wl.preload)
+    num_pages = used + headroom_pages
+    max_nodes = max(t.n_nodes for t in wl.traces)
+    per_layer = 2 * num_pages * shape.kv_heads * 16 * 128 * 2
+    free_b, total_b = torch.cuda.mem_get_info()
+    budget = free_b - (6 << 30)          # leave room for plans, workspaces, logs
+    fit = max(1, min(shape.layers, int(budget // per_layer)))
+    L = min(layers_alloc or shape.layers, fit)
+    log(f"[bench] pool: {num_pages} pages x {L} layers = {per_layer * L / 1e9:.1f} GB "
+        f"(HBM free {free_b / 1e9:.1f} GB of {total_b / 1e9:.1f} GB)")
+    shp = (L, num_pages, shape.kv_heads, 16, 128)
+    k_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    v_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    for l in range(L):
+        k_pool[l].normal_(0.0, shape.kv_scale, generator=g)
+        v_pool[l].normal_(0.0, shape.kv_scale, generator=g)
+    ctx = tim.Context(L, shape.q_heads, shape.kv_heads, num_pages, B, mp, max_nodes, pools=(k_pool, v_pool))
+    tables, free_ids = scattered_pages(seed, num_pages, 16, wl.preload)
+    pt = np.full((B, mp), -1, dtype=np.int32)
+    for b, t in enumerate(tables):
+        pt[b, : len(t)] = t
+    ctx.page_table.copy_(torch.from_numpy(pt))
+    ctx.seq_len.copy_(torch.tensor(wl.preload, dtype=torch.int32))
+    ctx.free_stack[: len(free_ids)] = torch.tensor(free_ids, dtype=torch.int32, device="cuda")
+    ctx.free_top.fill_(len(free_ids))
+    ops = np.asarray(wl.preload_ops(), dtype=np.int32).reshape(-1, 4)
+    ctx.tim_tree_mark(torch.from_numpy(ops).cuda())
+    assert ctx.tim_status() == 0
+    return ctx, L
+
+
+INT_STATE = ("page_table", "seq_len", "free_stack", "free_top", "status", "node_tok_begin", "node_sub_begin",
+             "node_sub_end", "node_tok_end", "node_list_order", "n_nodes", "lists_done")
+
+
+def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, record):
+    """Launches n_steps steps.  `record` (or None) collects events and length logs."""
+    L_alloc = ctx.cfg.layers
+    B = ctx.cfg.max_batch
+    hint_len, hint_step = max(wl.preload), 0
+    pending = []                                     # async length readbacks: (event, step, pinned tensor)
+    for step in range(n_steps):
+        ops = staged["ops"][step]
+        if ops is not None:
+            ctx.tim_tree_mark(ops)
+        ids = staged["flush"][step]
+        if ids is not None:
+            ctx.tim_prune_plan(ids, shape.threshold, plan)
+            reps = (layers_run + L_alloc - 1) // L_alloc
+            for r in range(reps):                    # reps == 1 unless the pool had to be aliased
+                ctx.tim_kv_compact(plan, 0, min(L_alloc, layers_run - r * L_alloc))
+            ctx.tim_plan_commit(plan)
+            if record is not None:
+                record["hdr"].append((step, len(ids), plan.hdr[: len(ids)].clone()))
+        ctx.tim_seq_advance()
+        if record is not None:
+            record["lens"][step].copy_(ctx.seq_len)
+        # length hint for the launch shape: newest finished readback + steps since (an upper bound)
+        while pending and pending[0][0].query():
+            _, s0, host = pending.pop(0)
+            hint_len, hint_step = int(host.max()), s0
+        hint = hint_len + (step - hint_step) + 1
+        for layer in range(layers_run):
+            la = layer % L_alloc
+            ctx.tim_kv_append(la, staged["k_new"][layer], staged["v_new"][layer])
+            if record is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            ctx.tim_decode_attn(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
+            if record is not None:
+                e1.record()
+                record["attn_events"].append((step, e0, e1))
+        host = staged["pinned"][step % len(staged["pinned"])]
+        host.copy_(ctx.seq_len, non_blocking=True)
+        ev = torch.cuda.Event()
+        ev.record()
+        pending.append((ev, step, host))
+        if len(pending) > len(staged["pinned"]) - 1:
+            pending[0][0].synchronize()
+
+
+def cpu_baseline(shape, seed):
+    """The oracle, as it stands, on a bounded sample of the same workload: 2 sequences of the
+    configuration-3 recipe, 1 layer, their big flush and 2 decode steps; scaled to whole steps."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import harness
+    from oracle.runtime import OracleRuntime
+    from paper_2507_16784_amd.workload import configs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    nseq, steps = 2, 2
+    _, wl = configs.config3(batch=nseq, steps=steps, seed=seed, stride=0, cadence=10**6)
+    cfg = harness.make_config(wl, layers=1, q_heads=shape.q_heads, kv_heads=shape.kv_heads, headroom_pages=1200)
+    rt = OracleRuntime(cfg, shape.threshold)
+    harness.preload_oracle(rt, wl, seed, shape.kv_scale)
+    q, k, v = harness.step_inputs(seed, 0, cfg, shape.kv_scale)
+    t0 = time.perf_counter()
+    rt.mark(wl.step_ops(0))
+    ev = rt.prune_plan(list(range(nseq)))
+    rt.kv_compact(ev, 0, 1)
+    rt.commit(ev)
+    t_event = (time.perf_counter() - t0) / nseq              # per sequence-layer flush
+    live_tokens = 0
+    t0 = time.perf_counter()
+    for s in range(steps):
+        rt.advance()
+        rt.append(0, k[0], v[0])
+        rt.decode_attn(0, q[0], shape.q_scale)
+        live_tokens += int(rt.seq_len.sum())
+    t_tok = (time.perf_counter() - t0) / live_tokens           # per live token-layer of attention
+    return dict(t_event_seq_layer=t_event, t_attn_token_layer=t_tok, threads=threads,
+                sample=f"{nseq} sequences x 1 layer of configuration 3: their big flush + {steps} decode steps")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--layers-alloc", type=int, default=0, help="debug: allocate fewer layer pools and alias them")
+    ap.add_argument("--seed", type=int, default=1000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path has no cross-GPU exchange and every box here has one GPU; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2507_16784_amd import tim
+    from paper_2507_16784_amd.workload import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t_setup = time.perf_counter()
+    shape, wl = configs.config3(batch=args.batch, steps=max(args.steps, args.warmup), seed=args.seed)
+    shape.q_scale = 128 ** -0.5
+    ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=4096, layers_alloc=args.layers_alloc,
+                                 seed=args.seed)
+    plan = tim.Plan(ctx.cfg, args.batch)
+    B = args.batch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(args.seed + 1)
+    rnd = lambda *s: (torch.randn(*s, generator=g, device="cuda") * shape.kv_scale).to(torch.bfloat16)
+    n_stage = max(args.steps, args.warmup)
+    staged = dict(
+        q=[rnd(B, shape.q_heads, 128) for _ in range(shape.layers)],
+        k_new=[rnd(B, shape.kv_heads, 128) for _ in range(shape.layers)],
+        v_new=[rnd(B, shape.kv_heads, 128) for _ in range(shape.layers)],
+        out=torch.empty(B, shape.q_heads, 128, dtype=torch.bfloat16, device="cuda"),
+        ops=[], flush=[],
+        pinned=[torch.empty(B, dtype=torch.int32, pin_memory=True) for _ in range(8)],
+    )
+    for s in range(n_stage):
+        ops = wl.step_ops(s)
+        staged["ops"].append(torch.tensor(ops, dtype=torch.int32, device="cuda").reshape(-1, 4) if ops else None)
+        ids = wl.flush_seqs(s)
+        staged["flush"].append(torch.tensor(ids, dtype=torch.int32, device="cuda") if ids else None)
+    initial = {n: getattr(ctx, n).clone() for n in INT_STATE}
+    torch.cuda.synchronize()
+    log(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; warmup {args.warmup}, timing {args.steps} steps")
+
+    run_steps(torch, tim, ctx, plan, shape, wl, staged, args.warmup, shape.layers, None)
+    torch.cuda.synchronize()
+    assert ctx.tim_status() == 0
+    for n, t in initial.items():                    # rewind the integer state; K/V content stays random
+        getattr(ctx, n).copy_(t)
+    record = dict(attn_events=[], hdr=[], lens=torch.zeros(args.steps, B, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, record)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    status = ctx.tim_status()
+    assert status == 0, f"device status {status}"
+
+    # ---- accounting (host, after the clock stopped) ----
+    lens = record["lens"].cpu().numpy().astype(np.int64)            # [steps][B], lengths attended
+    attn_bytes_step = lens.sum(axis=1) * KV_BYTES_PER_TOKEN_LAYER   # per layer launch
+    moved = pruned_n = pruned_m = 0
+    big_ratios = []
+    for step, n_ids, hdr in record["hdr"]:
+        h = hdr.cpu().numpy().astype(np.int64)
+        mv = np.maximum(h[:, tim.HDR_N_KEPT] - h[:, tim.HDR_KEEP_PAGES] * 16, 0)
+        moved += int(mv.sum())
+        for row in h:
+            if row[tim.HDR_N] - row[tim.HDR_N_KEPT] > row[tim.HDR_N] // 2:
+                big_ratios.append(1.0 - row[tim.HDR_N_KEPT] / row[tim.HDR_N])
+    bytes_attn = float(attn_bytes_step.sum()) * shape.layers
+    bytes_compact = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * shape.layers
+    bytes_append = args.steps * B * KV_BYTES_PER_TOKEN_LAYER * shape.layers
+    total_bytes = bytes_attn + bytes_compact + bytes_append
+    attn_ms = np.array([e0.elapsed_time(e1) for (_, e0, e1) in record["attn_events"]])
+    attn_bytes_launch = np.repeat(attn_bytes_step, shape.layers).astype(np.float64)
+    achieved = attn_bytes_launch.sum() / (attn_ms.sum() * 1e-3) / 1e9
+    steady = lens.max(axis=1) < 8192                                 # steps after every big flush
+    steady_launch = np.repeat(steady, shape.layers)
+    steps_per_s = args.steps / dt
+    res = {
+        "metric": METRIC, "value": round(steps_per_s, 3), "unit": "decode steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * dt / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "tokens_per_s": round(steps_per_s * B, 1),
+        "achieved_hbm_gbps": round(total_bytes / dt / 1e9, 1),
+        "hbm_frac_of_peak": round(total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 4),
+        "config": {"workload": shape.name, "batch": B, "layers": shape.layers, "layers_allocated": L_alloc,
+                   "q_heads": shape.q_heads, "kv_heads": shape.kv_heads, "head_dim": 128, "page_size": 16,
+                   "threshold": shape.threshold, "positions_per_seq": [int(min(wl.preload)), int(max(wl.preload))],
+                   "big_flushes": len(big_ratios),
+                   "mean_prune_ratio_big_flush": round(float(np.mean(big_ratios)), 4) if big_ratios else None,
+                   "moved_tokens": moved, "mean_live_tokens_per_seq": round(float(lens.mean()), 1),
+                   "bytes_per_step_GB": round(total_bytes / args.steps / 1e9, 3)},
+        "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_kernel (+ merge)",
+                     "achieved": round(float(achieved), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(float(achieved) / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "launches": int(attn_ms.size), "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2),
+                     "avg_bytes_per_launch": round(float(attn_bytes_launch.mean()), 1)},
+    }
+    if steady_launch.any():
+        res["roofline"]["steady_state_gbps"] = round(
+            float(attn_bytes_launch[steady_launch].sum() / (attn_ms[steady_launch].sum() * 1e-3) / 1e9), 1)
+    if not args.no_cpu_baseline:
+        cb = cpu_baseline(shape, args.seed)
+        flushes_per_step = sum(n for (_, n, _) in record["hdr"]) / args.steps
+        big_per_step = len(big_ratios) / args.steps
+        t_step = (float(lens.sum(axis=1).mean()) * shape.layers * cb["t_attn_token_layer"]
+                  + big_per_step * shape.layers * cb["t_event_seq_layer"])
+        res["cpu_baseline"] = {"value": round(1.0 / t_step, 6), "unit": "decode steps/s", "cores": cb["threads"],
+                               "kind": "oracle", "sample": cb["sample"] +
+                               "; per-token-layer and per-flush-layer times scaled to the timed window (extrapolated)"}
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

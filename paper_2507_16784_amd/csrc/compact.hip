@@ -26,19 +26,26 @@ __device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
-__global__ void __launch_bounds__(CP_THREADS)
-tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int layer_begin, int layer_end, double theta1,
-                   double theta8) {
-  const int e = blockIdx.y;
-  if (!pl.totals[TIM_TOT_OK]) return;
+// Work items are (destination page, layer group) pairs.  The destination pages of a flush
+// are exactly its fresh pages, numbered 0..total_need-1 in (sequence, page) order, so item
+// i belongs to the sequence whose PAGE_OFF range contains i; no work list is materialised
+// and the host never needs to know how much moved: a fixed grid strides over the items.
+__device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const tim_state &st, const tim_plan &pl,
+                                                 int n_seqs, int item, int l0, int l1, double theta1,
+                                                 double theta8) {
+  // sequence of this fresh page: last e with PAGE_OFF[e] <= item (n_seqs is small)
+  int lo = 0, hi = n_seqs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (pl.hdr[(int64_t)mid * TIM_PLAN_HDR + TIM_HDR_PAGE_OFF] <= item) lo = mid; else hi = mid - 1;
+  }
+  const int e = lo;
   const int32_t *hdr = pl.hdr + (int64_t)e * TIM_PLAN_HDR;
-  if (hdr[TIM_HDR_BAD]) return;
   const int m = hdr[TIM_HDR_N_KEPT], keep = hdr[TIM_HDR_KEEP_PAGES];
-  const int p = keep + blockIdx.x;
-  if (p * TIM_PS >= m) return;
+  const int p = keep + (item - hdr[TIM_HDR_PAGE_OFF]);
   const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
   const int j = p * TIM_PS + t;
-  if (j >= m) return;  // ragged last page; no block-wide sync below
+  if (hdr[TIM_HDR_BAD] || j >= m) return;  // ragged last page; no block-wide sync below
   const int T = cfg.max_pages_per_seq * TIM_PS;
   const int src = pl.src_slot[(int64_t)e * T + j];
   const int dst = pl.dst_slot[(int64_t)e * T + j];
@@ -66,8 +73,6 @@ tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int layer_begin, i
     }
   }
 
-  const int l0 = layer_begin + blockIdx.z * CP_LAYERS_PER_BLOCK;
-  const int l1 = min(l0 + CP_LAYERS_PER_BLOCK, layer_end);
   const uint4 *kp = reinterpret_cast<const uint4 *>(st.k_pool);
   const uint4 *vp = reinterpret_cast<const uint4 *>(st.v_pool);
   uint4 *kw = reinterpret_cast<uint4 *>(st.k_pool);
@@ -126,6 +131,19 @@ tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int layer_begin, i
   }
 }
 
+__global__ void __launch_bounds__(CP_THREADS)
+tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer_begin, int layer_end,
+                   double theta1, double theta8) {
+  if (!pl.totals[TIM_TOT_OK]) return;
+  const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
+  const int64_t n_work = (int64_t)pl.totals[TIM_TOT_NEED] * groups;
+  for (int64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
+    const int item = (int)(w / groups), grp = (int)(w % groups);
+    const int l0 = layer_begin + grp * CP_LAYERS_PER_BLOCK;
+    tim_compact_item(cfg, st, pl, n_seqs, item, l0, min(l0 + CP_LAYERS_PER_BLOCK, layer_end), theta1, theta8);
+  }
+}
+
 extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_begin, int32_t layer_end,
                               tim_stream stream) {
   if (!ctx || !ctx->bound || !plan || !plan->hdr || !plan->totals || !plan->src_slot || !plan->dst_slot ||
@@ -133,10 +151,10 @@ extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_
       layer_end > ctx->cfg.layers || layer_begin > layer_end)
     return TIM_ERR_INVALID_ARG;
   if (layer_begin == layer_end) return TIM_OK;
-  const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
-  dim3 grid(ctx->cfg.max_pages_per_seq, plan->n_seqs, groups);
+  // enough two-wave blocks to keep every CU's load queues full; they stride over the items
+  dim3 grid(16 * ctx->n_cu);
   hipLaunchKernelGGL(tim_compact_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
-                     layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
+                     plan->n_seqs, layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
   TIM_LAUNCH_CHECK();
   return TIM_OK;
 }
