@@ -102,14 +102,7 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
         for layer in range(layers_run):
             la = layer % L_alloc
             ctx.tim_kv_append(la, staged["k_new"][layer], staged["v_new"][layer])
-            if record is not None:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
             ctx.tim_decode_attn(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
-            if record is not None:
-                e1.record()
-                record["attn_events"].append((step, e0, e1))
         host = staged["pinned"][step % len(staged["pinned"])]
         host.copy_(ctx.seq_len, non_blocking=True)
         ev = torch.cuda.Event()
@@ -165,6 +158,7 @@ def main():
     ap.add_argument("--layers-alloc", type=int, default=0, help="debug: allocate fewer layer pools and alias them")
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dump", default="", help="write per-step lengths and attention timings to this .npz")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no cross-GPU exchange and every box here has one GPU; "
@@ -211,12 +205,16 @@ def main():
     assert ctx.tim_status() == 0
     for n, t in initial.items():                    # rewind the integer state; K/V content stays random
         getattr(ctx, n).copy_(t)
-    record = dict(attn_events=[], hdr=[], lens=torch.zeros(args.steps, B, dtype=torch.int32, device="cuda"))
+    record = dict(hdr=[], lens=torch.zeros(args.steps, B, dtype=torch.int32, device="cuda"))
+    # HIP events ride on the dispatch of every attention main kernel (on the launch stream)
+    ctx.tim_timing_begin(args.steps * shape.layers)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, record)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    attn_ms = np.array(ctx.tim_timing_end(), dtype=np.float64)
+    assert attn_ms.size == args.steps * shape.layers
     status = ctx.tim_status()
     assert status == 0, f"device status {status}"
 
@@ -236,7 +234,6 @@ def main():
     bytes_compact = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * shape.layers
     bytes_append = args.steps * B * KV_BYTES_PER_TOKEN_LAYER * shape.layers
     total_bytes = bytes_attn + bytes_compact + bytes_append
-    attn_ms = np.array([e0.elapsed_time(e1) for (_, e0, e1) in record["attn_events"]])
     attn_bytes_launch = np.repeat(attn_bytes_step, shape.layers).astype(np.float64)
     achieved = attn_bytes_launch.sum() / (attn_ms.sum() * 1e-3) / 1e9
     steady = lens.max(axis=1) < 8192                                 # steps after every big flush
@@ -256,12 +253,17 @@ def main():
                    "mean_prune_ratio_big_flush": round(float(np.mean(big_ratios)), 4) if big_ratios else None,
                    "moved_tokens": moved, "mean_live_tokens_per_seq": round(float(lens.mean()), 1),
                    "bytes_per_step_GB": round(total_bytes / args.steps / 1e9, 3)},
-        "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_kernel (+ merge)",
+        "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_mfma_kernel",
                      "achieved": round(float(achieved), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(float(achieved) / HBM_PEAK_GBPS, 4), "traffic": None,
                      "launches": int(attn_ms.size), "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2),
                      "avg_bytes_per_launch": round(float(attn_bytes_launch.mean()), 1)},
     }
+    step_ms = attn_ms.reshape(args.steps, shape.layers).sum(axis=1)
+    step_gbps = attn_bytes_step * shape.layers / (step_ms * 1e-3) / 1e9
+    res["roofline"]["per_step_gbps_p5_p50_p95"] = [round(float(x), 1) for x in np.percentile(step_gbps, [5, 50, 95])]
+    if args.dump:
+        np.savez(args.dump, lens=lens, attn_ms=attn_ms.reshape(args.steps, shape.layers), step_gbps=step_gbps)
     if steady_launch.any():
         res["roofline"]["steady_state_gbps"] = round(
             float(attn_bytes_launch[steady_launch].sum() / (attn_ms[steady_launch].sum() * 1e-3) / 1e9), 1)

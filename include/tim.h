@@ -243,6 +243,16 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
 /* out: device int32 [2] = (free pages, pages referenced by page tables). */
 int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream);
 
+/*
+ * Benchmark aid: between tim_timing_begin and tim_timing_end the main kernel of every
+ * tim_decode_attn call carries a pair of HIP events on its own dispatch (up to
+ * max_launches calls; later calls run untimed).  tim_timing_end waits for them, writes
+ * each launch's duration in milliseconds to ms_out (host, at least max_launches floats)
+ * and the count to n_out (host), and releases the events.  Host objects only.
+ */
+int tim_timing_begin(tim_ctx *ctx, int32_t max_launches);
+int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out);
+
 /* Waits for the stream, returns the sticky device status and clears it. */
 int tim_status(tim_ctx *ctx, tim_stream stream);
 

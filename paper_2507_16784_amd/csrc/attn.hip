@@ -1,6 +1,6 @@
 // Split-K paged GQA decode attention (HBM-bound: 4096 B per live token per layer).
 //
-// Work decomposition.  grid = (slots, kv_heads, batch).  A sequence's pages are cut into
+// Work decomposition.  grid = (batch * kv_heads, slots).  A sequence's pages are cut into
 // chunks of AT_CHUNK_PAGES pages; block `slot` takes chunks slot, slot + slots, ... and
 // accumulates them into one partial (m, l, o[128]) per query head of its group.  Inside a
 // chunk each of the four waves streams its own run of pages.  Fixed-size chunks keep a
@@ -13,6 +13,8 @@
 // of a DPP row.  Each lane row g keeps its own online-softmax state over the rows it
 // sees (4j + g), so the page loop has no cross-row traffic; rows, waves and chunks are
 // merged once at the end (log-sum-exp algebra), then a small kernel merges the slots.
+#include <hip/hip_ext.h>
+
 #include "tim_internal.h"
 
 #define AT_THREADS 256
@@ -50,12 +52,6 @@ struct AttnWs {
   float *o;   // [B][Hq][slots][128]
 };
 
-__device__ __forceinline__ int at_used_slots(int n, int slots) {
-  const int n_pages = (n + TIM_PS - 1) / TIM_PS;
-  const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  return min(nchunks, slots);
-}
-
 template <bool OUT_BF16>
 __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
   if (OUT_BF16) {
@@ -65,19 +61,63 @@ __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
   }
 }
 
+
+// Block epilogue shared by both variants.  The NS (m, l, o) states the block holds in LDS
+// are merged (log-sum-exp algebra).  If the block is the sequence's only one, the result is
+// final; otherwise it becomes this slot's partial for the merge kernel.  (Merging in the
+// last block to finish, behind an agent-scope counter, was measured and rejected: the
+// release/acquire fences it needs write back and invalidate the XCD's whole L2 per block
+// and cost 6x the kernel's run time.)
+template <int NS, bool OUT_BF16>
+__device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &ws, void *out, const float *red_m,
+                                          const float *red_l, const float *red_o, int b, int kvh, int slot, int slots,
+                                          int used) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int idx = tid + r * AT_THREADS;  // 0..511 = (h, dim)
+    const int h = idx >> 7, dim = idx & 127;
+    float mx = AT_NEG_BIG;
+#pragma unroll
+    for (int s2 = 0; s2 < NS; ++s2) mx = fmaxf(mx, red_m[s2 * TIM_G + h]);
+    float lt = 0.f, ot = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < NS; ++s2) {
+      const float sc = __builtin_amdgcn_exp2f(red_m[s2 * TIM_G + h] - mx);
+      lt = fmaf(red_l[s2 * TIM_G + h], sc, lt);
+      ot = fmaf(red_o[(s2 * TIM_G + h) * TIM_D + dim], sc, ot);
+    }
+    const int hq = kvh * TIM_G + h;
+    if (used == 1) {
+      at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, ot / lt);
+    } else {
+      const int64_t pi = ((int64_t)b * cfg.q_heads + hq) * slots + slot;
+      ws.o[pi * TIM_D + dim] = ot;
+      if (dim == 0) {
+        ws.ml[pi * 2] = mx;
+        ws.ml[pi * 2 + 1] = lt;
+      }
+    }
+  }
+}
+
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
-                        void *__restrict__ out, float scale_log2) {
+                        void *__restrict__ out, float scale_log2, int cpb) {
   __shared__ float red_m[AT_WAVES * 4][TIM_G];
   __shared__ float red_l[AT_WAVES * 4][TIM_G];
   __shared__ float red_o[AT_WAVES * 4][TIM_G][TIM_D];
 
-  const int slot = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, slots = gridDim.x;
+  // blockIdx.x = sequence * kv_heads + kv head: consecutive workgroup ids go to consecutive
+  // XCDs, so every XCD gets the same share of every sequence however unequal the lengths
+  const int slot = blockIdx.y, kvh = blockIdx.x % cfg.kv_heads, b = blockIdx.x / cfg.kv_heads, slots = gridDim.y;
   const int n = st.seq_len[b];
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  if (slot >= nchunks) return;  // uniform for the block
+  // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
+  const int used = min(slots, (nchunks + cpb - 1) / cpb);
+  if (slot >= used) return;  // uniform for the block
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
 
   // the group's four query rows, dims 8c..8c+7, pre-scaled so that exp2 gives softmax
@@ -104,7 +144,7 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
   const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
-  for (int chunk = slot; chunk < nchunks; chunk += slots) {
+  for (int chunk = slot; chunk < nchunks; chunk += used) {
     const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
     const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
     for (int pg = pg0; pg < pg1; ++pg) {
@@ -177,62 +217,286 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
     for (int e2 = 0; e2 < 8; ++e2) red_o[sidx][h][8 * c + e2] = acc[h][e2];
   }
   __syncthreads();
-  const int used = min(nchunks, slots);
+  at_finish<AT_WAVES * 4, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
+                                    used);
+}
+
+// ---- MFMA variant ---------------------------------------------------------------------
+// Same decomposition, but the two contractions run on the matrix cores
+// (v_mfma_f32_16x16x32_bf16: A[i][k] in lane i + 16*(k/8), element k%8; B[k][j] in lane
+// j + 16*(k/8); D[i][j] in lane j + 16*(i/4), register i%4).  A wave takes two pages
+// (32 tokens) per iteration.
+//   scores  S^T[token][head] = K[token][:] . Q[head][:]   A = K tile (16 tokens x 32 dims per
+//           step, 4 steps), B = Q^T with heads 4..15 zero.  Lane (g, j) = (lane/16, lane%16)
+//           loads 16 B of row j at dims 32s + 8g: each instruction reads 64 contiguous bytes
+//           of 16 rows, the four steps together the whole tile.  Lane (g, j<4) ends up with
+//           the scores of tokens 4g..4g+3 for head j, of both pages.
+//   values  O[head][dim] = P[head][token] . V[token][dim]   A = P: the eight probabilities a
+//           lane just computed are exactly its eight k-entries (k = 8g + e: page A tokens
+//           4g..4g+3, then page B's), so P never crosses lanes.  B = V: lane (g, c) loads the
+//           same eight token rows at dims 8c..8c+7 (full 256-byte rows per 16 lanes) and an
+//           in-register 8x8 transpose of 16-bit elements gives, for each of 8 MFMAs, its
+//           column "dim 8c + mf".  Output rows 0..3 (lanes 0..15) are the group's heads.
+// Softmax keeps one reference maximum per head, shared by the four lane groups, and only
+// renews it (cross-lane max, rescale of the accumulators) when a score exceeds it by more
+// than 2^8; until then p = exp2(t - ref) <= 256 is exact enough in bf16/fp32.  The row
+// sums stay per lane and are added once at the end.
+typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float at_f32x4 __attribute__((ext_vector_type(4)));
+typedef float at_f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t at_pack_bf16(float lo, float hi) {
+  at_f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, at_bf16x2));
+}
+__device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __builtin_bit_cast(at_bf16x8, u); }
+
+#define AT_LAZY_MAX 8.0f
+
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(AT_THREADS)
+tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
+                             void *__restrict__ out, float scale_log2, int cpb) {
+  __shared__ float red_m[AT_WAVES][TIM_G];
+  __shared__ float red_l[AT_WAVES][TIM_G];
+  __shared__ float red_o[AT_WAVES][TIM_G][TIM_D];
+
+  // blockIdx.x = sequence * kv_heads + kv head: consecutive workgroup ids go to consecutive
+  // XCDs, so every XCD gets the same share of every sequence however unequal the lengths
+  const int slot = blockIdx.y, kvh = blockIdx.x % cfg.kv_heads, b = blockIdx.x / cfg.kv_heads, slots = gridDim.y;
+  const int n = st.seq_len[b];
+  const int n_pages = (n + TIM_PS - 1) / TIM_PS;
+  const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
+  // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
+  const int used = min(slots, (nchunks + cpb - 1) / cpb);
+  if (slot >= used) return;  // uniform for the block
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+
+  // B operand of the score product: Q^T, head j (zero for j >= 4), dims 32s + 8g .. +8
+  uint4 qb[4];
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int idx = tid + r * AT_THREADS;  // 0..511 = (h, dim)
-    const int h = idx >> 7, dim = idx & 127;
-    float mx = AT_NEG_BIG;
+  for (int s = 0; s < 4; ++s) {
+    qb[s] = make_uint4(0, 0, 0, 0);
+    if (j < TIM_G) qb[s] = q[((int64_t)b * cfg.q_heads + kvh * TIM_G + j) * 16 + 4 * s + g];
+  }
+  const float lane_bias = j < TIM_G ? 0.f : -INFINITY;  // padded heads never contribute
+
+  float m_ref = AT_NEG_BIG, l_part = 0.f;
+  at_f32x4 acc[8];
 #pragma unroll
-    for (int s2 = 0; s2 < AT_WAVES * 4; ++s2) mx = fmaxf(mx, red_m[s2][h]);
-    float lt = 0.f, ot = 0.f;
+  for (int mf = 0; mf < 8; ++mf) acc[mf] = (at_f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const uint4 *kpool = reinterpret_cast<const uint4 *>(st.k_pool);
+  const uint4 *vpool = reinterpret_cast<const uint4 *>(st.v_pool);
+  const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
+  const int64_t layer_base = (int64_t)layer * cfg.num_pages;
+
+  for (int chunk = slot; chunk < nchunks; chunk += used) {
+    const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
+    const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
+    // the wave's page ids of this chunk in one load: lane i holds page pg0 + i
+    const int my_pid = ptab[min(pg0 + (lane & (AT_PAGES_PER_WAVE - 1)), max(n_pages - 1, 0))];
+    for (int pg = pg0; pg < pg1; pg += 2) {
+      const bool has_b = pg + 1 < pg1;
+      int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
+      int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
+      if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
+        tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
+        phys_a = phys_b = 0;
+      }
+      const int64_t tile_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+      const int64_t tile_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+      uint4 ka[4], kb[4], va[4], vb[4];
 #pragma unroll
-    for (int s2 = 0; s2 < AT_WAVES * 4; ++s2) {
-      const float sc = __builtin_amdgcn_exp2f(red_m[s2][h] - mx);
-      lt = fmaf(red_l[s2][h], sc, lt);
-      ot = fmaf(red_o[s2][h][dim], sc, ot);
-    }
-    const int hq = kvh * TIM_G + h;
-    if (used == 1) {  // the only partial of this sequence: finish here
-      at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, ot / lt);
-    } else {
-      const int64_t pi = ((int64_t)b * cfg.q_heads + hq) * slots + slot;
-      ws.o[pi * TIM_D + dim] = ot;
-      if (dim == 0) {
-        ws.ml[pi * 2] = mx;
-        ws.ml[pi * 2 + 1] = lt;
+      for (int s = 0; s < 4; ++s) ka[s] = kpool[tile_a + j * 16 + 4 * s + g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kb[s] = kpool[tile_b + j * 16 + 4 * s + g];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) va[i] = vpool[tile_a + (4 * g + i) * 16 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vb[i] = vpool[tile_b + (4 * g + i) * 16 + j];
+
+      // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
+      const int left_a = n - pg * TIM_PS;
+      const int left_b = has_b ? n - (pg + 1) * TIM_PS : 0;
+      const bool full = left_b >= TIM_PS;  // then page A is full as well
+
+      at_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(ka[s]), at_as_bf16x8(qb[s]), sa, 0, 0, 0);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(kb[s]), at_as_bf16x8(qb[s]), sb, 0, 0, 0);
+
+      float t[8];
+      if (full) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          t[r] = fmaf(sa[r], scale_log2, lane_bias);
+          t[4 + r] = fmaf(sb[r], scale_log2, lane_bias);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool ok_a = 4 * g + r < left_a, ok_b = 4 * g + r < left_b;
+          // the select is on the product: a stale row may hold anything, also NaN or Inf
+          t[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
+          t[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
+          if (!ok_a) va[r] = make_uint4(0, 0, 0, 0);
+          if (!ok_b) vb[r] = make_uint4(0, 0, 0, 0);
+        }
+      }
+      float lm = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+      if (__any(lm > m_ref + AT_LAZY_MAX)) {
+        // renew the reference: maximum over the four lane groups of each head column
+        float x = lm;
+        x = fmaxf(x, __shfl_xor(x, 16, 64));
+        x = fmaxf(x, __shfl_xor(x, 32, 64));
+        const float m_new = fmaxf(m_ref, x);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        l_part *= alpha;
+        m_ref = m_new;
+        // accumulator row r (head r) lives in lanes 0..15; its factor sits in lane r
+        float ar[TIM_G];
+#pragma unroll
+        for (int r = 0; r < TIM_G; ++r) ar[r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(alpha), r));
+#pragma unroll
+        for (int mf = 0; mf < 8; ++mf)
+#pragma unroll
+          for (int r = 0; r < TIM_G; ++r) acc[mf][r] *= ar[r];
+      }
+      float p[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(t[e] - m_ref);
+        l_part += p[e];
+      }
+      uint4 pw;
+      pw.x = at_pack_bf16(p[0], p[1]);
+      pw.y = at_pack_bf16(p[2], p[3]);
+      pw.z = at_pack_bf16(p[4], p[5]);
+      pw.w = at_pack_bf16(p[6], p[7]);
+      const at_bf16x8 pa = at_as_bf16x8(pw);
+
+      // 8x8 transpose of 16-bit elements: rows = token slots (A0..A3, B0..B3), columns = dims
+      const uint32_t *ra[8] = {&va[0].x, &va[1].x, &va[2].x, &va[3].x, &vb[0].x, &vb[1].x, &vb[2].x, &vb[3].x};
+#pragma unroll
+      for (int mf = 0; mf < 8; ++mf) {
+        uint4 col;
+        uint32_t *cw = &col.x;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t x0 = ra[2 * u][mf >> 1], x1 = ra[2 * u + 1][mf >> 1];
+          cw[u] = (mf & 1) ? __builtin_amdgcn_perm(x1, x0, 0x07060302u) : __builtin_amdgcn_perm(x1, x0, 0x05040100u);
+        }
+        acc[mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, at_as_bf16x8(col), acc[mf], 0, 0, 0);
       }
     }
   }
+
+  // row sums: add the four lane groups of each head column
+  l_part += __shfl_xor(l_part, 16, 64);
+  l_part += __shfl_xor(l_part, 32, 64);
+  if (lane < TIM_G) {
+    red_m[w][lane] = m_ref;
+    red_l[w][lane] = l_part;
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int r = 0; r < TIM_G; ++r)
+#pragma unroll
+      for (int mf = 0; mf < 8; ++mf) red_o[w][r][8 * lane + mf] = acc[mf][r];
+  }
+  __syncthreads();
+  at_finish<AT_WAVES, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
+                                used);
 }
 
-// Log-sum-exp merge of the slot partials of one (sequence, query head).
+// Log-sum-exp merge of the slot partials: one block per (sequence, kv head), its 512
+// (head, dim) outputs two per thread, one online pass over the slots.
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(TIM_D)
-tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict__ out, int slots) {
-  const int bh = blockIdx.x, b = bh / cfg.q_heads, dim = threadIdx.x;
+__global__ void __launch_bounds__(AT_THREADS)
+tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict__ out, int slots, int cpb) {
+  const int kvh = blockIdx.x, b = blockIdx.y;
   const int n = st.seq_len[b];
-  const int used = at_used_slots(n, slots);
+  const int n_pages = (n + TIM_PS - 1) / TIM_PS;
+  const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
+  const int used = min(slots, (nchunks + cpb - 1) / cpb);
   if (used == 1) return;  // written by the partial kernel
-  if (used == 0) {        // empty working memory: defined as zero
-    at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + dim, 0.f);
-    return;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int idx = threadIdx.x + r * AT_THREADS;
+    const int hq = kvh * TIM_G + (idx >> 7), dim = idx & 127;
+    const int64_t o_idx = ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim;
+    if (used == 0) {  // empty working memory: defined as zero
+      at_store_out<OUT_BF16>(out, o_idx, 0.f);
+      continue;
+    }
+    const int64_t p0 = ((int64_t)b * cfg.q_heads + hq) * slots;
+    float mx = AT_NEG_BIG, lt = 0.f, ot = 0.f;
+    for (int s = 0; s < used; ++s) {
+      const float ms = ws.ml[(p0 + s) * 2], ls = ws.ml[(p0 + s) * 2 + 1], os = ws.o[(p0 + s) * TIM_D + dim];
+      const float mn = fmaxf(mx, ms);
+      const float a = __builtin_amdgcn_exp2f(mx - mn), c = __builtin_amdgcn_exp2f(ms - mn);
+      lt = fmaf(lt, a, ls * c);
+      ot = fmaf(ot, a, os * c);
+      mx = mn;
+    }
+    at_store_out<OUT_BF16>(out, o_idx, ot / lt);
   }
-  const int64_t p0 = (int64_t)bh * slots;
-  float mx = AT_NEG_BIG;
-  for (int s = 0; s < used; ++s) mx = fmaxf(mx, ws.ml[(p0 + s) * 2]);
-  float lt = 0.f, ot = 0.f;
-  for (int s = 0; s < used; ++s) {
-    const float sc = __builtin_amdgcn_exp2f(ws.ml[(p0 + s) * 2] - mx);
-    lt = fmaf(ws.ml[(p0 + s) * 2 + 1], sc, lt);
-    ot = fmaf(ws.o[(p0 + s) * TIM_D + dim], sc, ot);
-  }
-  at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + dim, ot / lt);
 }
 
 extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
   if (!cfg) return 0;
   return (int64_t)cfg->max_batch * cfg->q_heads * AT_MAX_SLOTS * (TIM_D + 2) * (int64_t)sizeof(float);
+}
+
+template <bool MFMA, bool OUT_BF16>
+static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
+                      float scale_log2, int cpb) {
+  auto kernel = MFMA ? tim_attn_partial_mfma_kernel<OUT_BF16> : tim_attn_partial_kernel<OUT_BF16>;
+  const uint4 *q4 = reinterpret_cast<const uint4 *>(q);
+  if (ctx->timing_on && ctx->timing_n < (int)ctx->ev_start.size()) {
+    // events attached to the dispatch itself: the kernel's own begin/end, no extra barrier
+    const int i = ctx->timing_n++;
+    hipExtLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->ev_start[i], ctx->ev_stop[i], 0, ctx->cfg, ctx->st,
+                          ws, layer, q4, out, scale_log2, cpb);
+  } else {
+    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb);
+  }
+}
+
+extern "C" int tim_timing_begin(tim_ctx *ctx, int32_t max_launches) {
+  if (!ctx || max_launches <= 0 || ctx->timing_on) return TIM_ERR_INVALID_ARG;
+  ctx->ev_start.resize(max_launches);
+  ctx->ev_stop.resize(max_launches);
+  for (int i = 0; i < max_launches; ++i) {
+    TIM_HIP_CHECK(hipEventCreate(&ctx->ev_start[i]));
+    TIM_HIP_CHECK(hipEventCreate(&ctx->ev_stop[i]));
+  }
+  ctx->timing_n = 0;
+  ctx->timing_on = true;
+  return TIM_OK;
+}
+
+extern "C" int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out) {
+  if (!ctx || !ctx->timing_on || !ms_out || !n_out) return TIM_ERR_INVALID_ARG;
+  int rc = TIM_OK;
+  for (int i = 0; i < ctx->timing_n; ++i) {
+    if (hipEventSynchronize(ctx->ev_stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms_out[i], ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess)
+      rc = TIM_ERR_HIP;
+  }
+  *n_out = ctx->timing_n;
+  for (size_t i = 0; i < ctx->ev_start.size(); ++i) {
+    (void)hipEventDestroy(ctx->ev_start[i]);
+    (void)hipEventDestroy(ctx->ev_stop[i]);
+  }
+  ctx->ev_start.clear();
+  ctx->ev_stop.clear();
+  ctx->timing_on = false;
+  ctx->timing_n = 0;
+  return rc;
 }
 
 extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
@@ -246,31 +510,32 @@ extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void 
   const int max_pages = (bound + TIM_PS - 1) / TIM_PS;
   const int nchunks = (max_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
   const int rows = cfg.max_batch * cfg.kv_heads;
-  const int slots_occ = (8 * ctx->n_cu + rows - 1) / rows;  // enough blocks to fill the chip
-  const int slots_len = (nchunks + 3) / 4;                  // at most four chunks per block
-  int slots = slots_occ > slots_len ? slots_occ : slots_len;
-  if (slots > nchunks) slots = nchunks;
+  // chunks per block: as many as still leave enough blocks to fill the chip several times
+  int cpb = ctx->attn_cpb;
+  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < 8 * (int64_t)ctx->n_cu) --cpb;
+  int slots = (nchunks + cpb - 1) / cpb;
   if (slots > AT_MAX_SLOTS) slots = AT_MAX_SLOTS;
   if (slots < 1) slots = 1;
   AttnWs ws;
   ws.ml = ctx->st.attn_ws;
-  ws.o = ctx->st.attn_ws + (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * 2;
+  ws.o = ws.ml + (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * 2;
   const float scale_log2 = sm_scale * 1.4426950408889634f;
   hipStream_t s = tim_hs(stream);
-  dim3 grid(slots, cfg.kv_heads, cfg.max_batch);
-  if (out_dtype == TIM_OUT_BF16) {
-    hipLaunchKernelGGL(tim_attn_partial_kernel<true>, grid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, layer,
-                       reinterpret_cast<const uint4 *>(q), out, scale_log2);
-    TIM_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tim_attn_merge_kernel<true>, dim3(cfg.max_batch * cfg.q_heads), dim3(TIM_D), 0, s, cfg,
-                       ctx->st, ws, out, slots);
+  dim3 grid(cfg.max_batch * cfg.kv_heads, slots);
+  const bool bf = out_dtype == TIM_OUT_BF16;
+  if (ctx->attn_impl == 1) {
+    if (bf) at_launch<true, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    else at_launch<true, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
   } else {
-    hipLaunchKernelGGL(tim_attn_partial_kernel<false>, grid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, layer,
-                       reinterpret_cast<const uint4 *>(q), out, scale_log2);
-    TIM_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tim_attn_merge_kernel<false>, dim3(cfg.max_batch * cfg.q_heads), dim3(TIM_D), 0, s, cfg,
-                       ctx->st, ws, out, slots);
+    if (bf) at_launch<false, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    else at_launch<false, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
   }
   TIM_LAUNCH_CHECK();
+  if (slots > 1) {  // with one slot every block has already written its final output
+    dim3 mgrid(cfg.kv_heads, cfg.max_batch);
+    if (bf) hipLaunchKernelGGL((tim_attn_merge_kernel<true>), mgrid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, out, slots, cpb);
+    else hipLaunchKernelGGL((tim_attn_merge_kernel<false>), mgrid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, out, slots, cpb);
+    TIM_LAUNCH_CHECK();
+  }
   return TIM_OK;
 }

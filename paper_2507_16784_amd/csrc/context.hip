@@ -1,5 +1,7 @@
 // Context object: configuration, the caller's buffer pointers, host-side constants.
 #include <cmath>
+#include <cstdlib>
+#include <cstring>
 #include <new>
 
 #include "tim_internal.h"
@@ -19,6 +21,14 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   c->cfg = *cfg;
   c->bound = false;
   c->n_cu = 256;
+  c->attn_impl = 1;
+  c->attn_cpb = 4;
+  if (const char *v = std::getenv("TIM_ATTN_CPB")) {  // tuning experiments only
+    const int x = std::atoi(v);
+    if (x >= 1 && x <= 64) c->attn_cpb = x;
+  }
+  if (const char *v = std::getenv("TIM_ATTN_IMPL"))  // debugging / A-B measurement only
+    c->attn_impl = std::strcmp(v, "valu") == 0 ? 0 : 1;
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)

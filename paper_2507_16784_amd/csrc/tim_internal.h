@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "tim.h"
 
 #define TIM_D 128          // head dim
@@ -17,7 +19,12 @@ struct tim_ctx {
   tim_state st;
   bool bound;
   int n_cu;
+  int attn_impl;  // 1 = matrix-core attention (default), 0 = vector-ALU attention
+  int attn_cpb;   // target chunks per attention block
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
+  bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
+  int timing_n = 0;
+  std::vector<hipEvent_t> ev_start, ev_stop;
 };
 
 struct RopeFreq {

@@ -22,7 +22,7 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE = range(5)
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_decode_attn", "tim_pool_stats", "tim_status"]
+           "tim_decode_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
 class tim_config(C.Structure):
@@ -66,6 +66,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_pool_stats": (C.c_int, [p, p, p]),
         "tim_status": (C.c_int, [p, p]),
+        "tim_timing_begin": (C.c_int, [p, i32]),
+        "tim_timing_end": (C.c_int, [p, C.POINTER(f32), C.POINTER(i32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -221,3 +223,14 @@ class Context:
 
     def tim_status(self) -> int:
         return lib().tim_status(self.handle, _stream())
+
+    def tim_timing_begin(self, max_launches: int):
+        self._timing_cap = max_launches
+        _check(lib().tim_timing_begin(self.handle, max_launches), "tim_timing_begin")
+
+    def tim_timing_end(self):
+        """Durations (ms) of the attention main kernel of each timed tim_decode_attn call."""
+        buf = (C.c_float * self._timing_cap)()
+        n = C.c_int32(0)
+        _check(lib().tim_timing_end(self.handle, buf, C.byref(n)), "tim_timing_end")
+        return list(buf[: n.value])
