@@ -412,38 +412,63 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
                                 used);
 }
 
-// Log-sum-exp merge of the slot partials: one block per (sequence, kv head), its 512
-// (head, dim) outputs two per thread, one online pass over the slots.
+// Log-sum-exp merge of the slot partials: one block of 128 threads per (sequence, query
+// head).  Thread s first turns slot s's (m, l) into a weight 2^(m_s - max) held in LDS;
+// then thread d sums the weighted o_s[d] over the slots with independent, unrolled loads.
+__device__ __forceinline__ float at_wave_max(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+  return v;
+}
+__device__ __forceinline__ float at_wave_sum(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(AT_THREADS)
+__global__ void __launch_bounds__(TIM_D)
 tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict__ out, int slots, int cpb) {
-  const int kvh = blockIdx.x, b = blockIdx.y;
+  __shared__ float wgt[AT_MAX_SLOTS];
+  __shared__ float red[4];
+  const int bh = blockIdx.x, b = bh / cfg.q_heads, tid = threadIdx.x;
   const int n = st.seq_len[b];
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
   const int used = min(slots, (nchunks + cpb - 1) / cpb);
   if (used == 1) return;  // written by the partial kernel
-#pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int idx = threadIdx.x + r * AT_THREADS;
-    const int hq = kvh * TIM_G + (idx >> 7), dim = idx & 127;
-    const int64_t o_idx = ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim;
-    if (used == 0) {  // empty working memory: defined as zero
-      at_store_out<OUT_BF16>(out, o_idx, 0.f);
-      continue;
-    }
-    const int64_t p0 = ((int64_t)b * cfg.q_heads + hq) * slots;
-    float mx = AT_NEG_BIG, lt = 0.f, ot = 0.f;
-    for (int s = 0; s < used; ++s) {
-      const float ms = ws.ml[(p0 + s) * 2], ls = ws.ml[(p0 + s) * 2 + 1], os = ws.o[(p0 + s) * TIM_D + dim];
-      const float mn = fmaxf(mx, ms);
-      const float a = __builtin_amdgcn_exp2f(mx - mn), c = __builtin_amdgcn_exp2f(ms - mn);
-      lt = fmaf(lt, a, ls * c);
-      ot = fmaf(ot, a, os * c);
-      mx = mn;
-    }
-    at_store_out<OUT_BF16>(out, o_idx, ot / lt);
+  if (used == 0) {        // empty working memory: defined as zero
+    at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, 0.f);
+    return;
   }
+  const int64_t p0 = (int64_t)bh * slots;
+  float m = AT_NEG_BIG, l = 0.f;
+  if (tid < used) {
+    m = ws.ml[(p0 + tid) * 2];
+    l = ws.ml[(p0 + tid) * 2 + 1];
+  }
+  const float wm = at_wave_max(m);
+  if ((tid & 63) == 0) red[tid >> 6] = wm;
+  __syncthreads();
+  const float mx = fmaxf(red[0], red[1]);
+  const float w = tid < used ? __builtin_amdgcn_exp2f(m - mx) : 0.f;
+  wgt[tid] = w;
+  const float ws_l = at_wave_sum(w * l);
+  if ((tid & 63) == 0) red[2 + (tid >> 6)] = ws_l;
+  __syncthreads();
+  const float lt = red[2] + red[3];
+  const float *o = ws.o + p0 * TIM_D + tid;
+  float acc = 0.f;
+  int s = 0;
+  for (; s + 8 <= used; s += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc = fmaf(v[u], wgt[s + u], acc);
+  }
+  for (; s < used; ++s) acc = fmaf(o[(int64_t)s * TIM_D], wgt[s], acc);
+  at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, acc / lt);
 }
 
 extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
@@ -532,9 +557,9 @@ extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void 
   }
   TIM_LAUNCH_CHECK();
   if (slots > 1) {  // with one slot every block has already written its final output
-    dim3 mgrid(cfg.kv_heads, cfg.max_batch);
-    if (bf) hipLaunchKernelGGL((tim_attn_merge_kernel<true>), mgrid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, out, slots, cpb);
-    else hipLaunchKernelGGL((tim_attn_merge_kernel<false>), mgrid, dim3(AT_THREADS), 0, s, cfg, ctx->st, ws, out, slots, cpb);
+    dim3 mgrid(cfg.max_batch * cfg.q_heads);
+    if (bf) hipLaunchKernelGGL((tim_attn_merge_kernel<true>), mgrid, dim3(TIM_D), 0, s, cfg, ctx->st, ws, out, slots, cpb);
+    else hipLaunchKernelGGL((tim_attn_merge_kernel<false>), mgrid, dim3(TIM_D), 0, s, cfg, ctx->st, ws, out, slots, cpb);
     TIM_LAUNCH_CHECK();
   }
   return TIM_OK;
