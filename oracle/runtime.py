@@ -206,8 +206,9 @@ class OracleRuntime:
             self.page_table[b] = sp.new_table
             self.seq_len[b] = pl.n_kept
             for arr in (self.tok_begin, self.sub_begin, self.sub_end, self.tok_end):
-                row = arr[b, : self.n_nodes[b]]
-                arr[b, : self.n_nodes[b]] = [pl.remap_boundary(int(x)) for x in row]
+                row = arr[b, : self.n_nodes[b]]                   # a view: boundaries of this sequence's nodes
+                set_ = row >= 0                                   # -1 (not reached yet) stays -1
+                row[set_] = pl.rank[row[set_]]                    # boundary t -> survivors before t
 
     # ---- attention ---------------------------------------------------------
     def decode_attn(self, layer: int, q: np.ndarray, scale: float) -> np.ndarray:
