@@ -125,8 +125,8 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
 
 
 def cpu_baseline(shape, seed):
-    """The oracle, as it stands, on a bounded sample of the same workload: 2 sequences of the
-    configuration-3 recipe, 1 layer, their big flush and 2 decode steps; scaled to whole steps."""
+    """The oracle, as it stands, on a bounded sample of the same workload: 4 sequences of the
+    configuration-3 recipe, 1 layer, their big flush and 8 decode steps; scaled to whole steps."""
     import numpy as np
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import harness
@@ -137,7 +137,7 @@ def cpu_baseline(shape, seed):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = 1
-    nseq, steps = 2, 2
+    nseq, steps = 4, 8
     _, wl = configs.config3(batch=nseq, steps=steps, seed=seed, stride=0, cadence=10**6)
     cfg = harness.make_config(wl, layers=1, q_heads=shape.q_heads, kv_heads=shape.kv_heads, headroom_pages=1200)
     rt = OracleRuntime(cfg, shape.threshold)
