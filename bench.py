@@ -7,7 +7,11 @@ then per layer KV append + paged GQA decode attention.  The workload is configur
 (batch 64, 36 layers, 32/8 heads, trees of 16K-32K positions, ~90 % pruned by each
 sequence's big flush), synthetic and seeded, resident in HBM before the clock starts.
 
-Prints ONE JSON line; see the design doc for the definition of every field.
+Prints ONE JSON line.  value = steps / wall time of the timed region; achieved_hbm_gbps =
+(attention + 2 x compaction + append algorithmic bytes) / the same wall time; roofline =
+the attention main kernel alone: 4096 B per live token per layer over the kernel's own
+dispatch-attached HIP event durations, against the 8 TB/s HBM peak; cpu_baseline = the CPU
+oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
