@@ -139,6 +139,9 @@ enum {
   TIM_HDR_PUSH = 7,         /* old pages returned */
   TIM_HDR_PUSH_OFF = 8,     /* exclusive sum of PUSH over earlier sequences */
   TIM_HDR_BAD = 9,          /* 1 = tree rejected, sequence left untouched */
+  TIM_HDR_EXT = 10,         /* survivors after the first pruned token: m - first_pruned (0 if nothing moved) */
+  TIM_HDR_EXT_OFF = 11,     /* exclusive sum of EXT over earlier sequences */
+  TIM_HDR_EXT_TILE_OFF = 12,/* exclusive sum of ceil(EXT / 32) over earlier sequences */
   TIM_PLAN_HDR = 16
 };
 enum {
@@ -147,6 +150,8 @@ enum {
   TIM_TOT_PUSH = 2,
   TIM_TOT_TOP_AFTER_POP = 3,
   TIM_TOT_TOP_BEFORE = 4,
+  TIM_TOT_EXT = 5,       /* sum of EXT */
+  TIM_TOT_EXT_TILES = 6, /* sum of ceil(EXT / 32) */
   TIM_PLAN_TOTALS = 8
 };
 
@@ -239,6 +244,22 @@ int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream stream);
  */
 int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                     int32_t max_seq_len, tim_stream stream);
+
+/*
+ * Attention half of the paper's own repositioning (Eq. 1, f_extend): after a flush is
+ * committed, every survivor behind the first pruned token of a flushed sequence is
+ * "extended", i.e. attends causally to the untouched prefix, the earlier extended tokens
+ * and itself.  For flushed sequence e (row e of the plan) and j in [first_pruned, m):
+ *   out[off_e + j - first_pruned][h] = softmax(sm_scale * q[..][h] . K[0..j]^T) V[0..j]
+ * over the sequence's current cache, with off_e = TIM_HDR_EXT_OFF of row e.  q_ext: device
+ * bf16 [TIM_TOT_EXT][q_heads][128], rotated at the new positions; out_ext: device, same
+ * shape, out_dtype.  n_ext_total must equal the plan's TIM_TOT_EXT (the caller reads it
+ * back to build the queries); a smaller value leaves the tail uncomputed, a larger one is
+ * harmless.  Weight-free: it does not recompute K/V, it is the attention the re-encoding
+ * would run, so its cost can be set against tim_kv_compact's re-rotation.
+ */
+int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan, const void *q_ext, void *out_ext,
+                    int32_t n_ext_total, float sm_scale, int32_t out_dtype, tim_stream stream);
 
 /* out: device int32 [2] = (free pages, pages referenced by page tables). */
 int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream);

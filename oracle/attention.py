@@ -26,3 +26,16 @@ def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float) -> np.ndar
         p = p / p.sum()
         out[h] = p @ vh
     return out
+
+
+def extend(q_ext: np.ndarray, k: np.ndarray, v: np.ndarray, first_pos: int, scale: float) -> np.ndarray:
+    """Attention of re-encoding ("extending") a run of tokens, by definition (paper Eq. 1):
+    extended token i sits at position first_pos + i and attends causally to every cached
+    position up to and including its own.  q_ext [E, Hq, D], k/v [T, Hkv, D] with
+    T >= first_pos + E, all float64 -> out [E, Hq, D] float64."""
+    e = q_ext.shape[0]
+    out = np.empty(q_ext.shape, dtype=np.float64)
+    for i in range(e):
+        j = first_pos + i
+        out[i] = attend(q_ext[i], k[: j + 1], v[: j + 1], scale)
+    return out

@@ -15,7 +15,7 @@ from dataclasses import dataclass
 import numpy as np
 
 from . import bf16
-from .attention import attend
+from .attention import attend, extend
 from .pages import FreeStack
 from .plan import Plan
 from .prune_rule import PruningBuffer, kept_flags
@@ -218,6 +218,21 @@ class OracleRuntime:
         for b in range(c.max_batch):
             kb, vb = self.gather_kv(layer, b)
             out[b] = attend(bf16.to_f64(q[b]), bf16.to_f64(kb), bf16.to_f64(vb), scale)
+        return out
+
+    def extend_attn(self, layer: int, ev: EventPlan, q_ext: np.ndarray, scale: float) -> np.ndarray:
+        """Attention half of Eq. 1 after `ev` was committed.  q_ext: bf16 bits [E_total, Hq, D],
+        the extended tokens of the flushed sequences in ascending sequence order, each run
+        covering new positions first_pruned .. m-1.  Returns float32 of the same shape."""
+        out = np.zeros(q_ext.shape, dtype=np.float32)
+        at = 0
+        for sp in ev.seqs:
+            f, m = sp.plan.first_pruned, sp.plan.n_kept
+            e = max(m - f, 0)
+            if e:
+                kb, vb = self.gather_kv(layer, sp.seq)
+                out[at : at + e] = extend(bf16.to_f64(q_ext[at : at + e]), bf16.to_f64(kb), bf16.to_f64(vb), f, scale)
+            at += e
         return out
 
     # ---- accounting ----------------------------------------------------------

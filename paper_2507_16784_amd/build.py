@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtim.so")
-SOURCES = ["context.hip", "pool.hip", "plan.hip", "compact.hip", "attn.hip"]
+SOURCES = ["context.hip", "pool.hip", "plan.hip", "compact.hip", "attn.hip", "extend.hip"]
 
 
 def hipcc() -> str:

@@ -137,29 +137,38 @@ tim_plan_scan_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *_
     hdr[TIM_HDR_KEEP_PAGES] = keep;
     hdr[TIM_HDR_NEED] = (m + TIM_PS - 1) / TIM_PS - keep;
     hdr[TIM_HDR_PUSH] = (n + TIM_PS - 1) / TIM_PS - keep;
+    hdr[TIM_HDR_EXT] = m - f;  // survivors behind the first pruned token (0 when nothing moves)
   }
 }
 
 __global__ void __launch_bounds__(1024) tim_plan_pages_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs) {
   __shared__ int smem[17];
   const int tid = threadIdx.x;
-  int need_base = 0, push_base = 0;
+  int need_base = 0, push_base = 0, ext_base = 0, tile_base = 0;
   for (int e0 = 0; e0 < n_seqs; e0 += blockDim.x) {
     const int e = e0 + tid;
-    int need = 0, push = 0;
+    int need = 0, push = 0, ext = 0;
     if (e < n_seqs) {
       need = pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_NEED];
       push = pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_PUSH];
+      ext = pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_EXT];
     }
-    int nt, pt;
+    const int tiles = (ext + 31) / 32;
+    int nt, pt, et, tt;
     const int ni = tim_block_incl_scan(need, smem, &nt);
     const int pi = tim_block_incl_scan(push, smem, &pt);
+    const int ei = tim_block_incl_scan(ext, smem, &et);
+    const int ti = tim_block_incl_scan(tiles, smem, &tt);
     if (e < n_seqs) {
       pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_PAGE_OFF] = need_base + ni - need;
       pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_PUSH_OFF] = push_base + pi - push;
+      pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_EXT_OFF] = ext_base + ei - ext;
+      pl.hdr[(int64_t)e * TIM_PLAN_HDR + TIM_HDR_EXT_TILE_OFF] = tile_base + ti - tiles;
     }
     need_base += nt;
     push_base += pt;
+    ext_base += et;
+    tile_base += tt;
   }
   if (tid == 0) {
     const int top = *st.free_top;
@@ -169,6 +178,8 @@ __global__ void __launch_bounds__(1024) tim_plan_pages_kernel(tim_config cfg, ti
     pl.totals[TIM_TOT_PUSH] = push_base;
     pl.totals[TIM_TOT_TOP_BEFORE] = top;
     pl.totals[TIM_TOT_TOP_AFTER_POP] = ok ? top - need_base : top;
+    pl.totals[TIM_TOT_EXT] = ext_base;
+    pl.totals[TIM_TOT_EXT_TILES] = tile_base;
     if (ok)
       *st.free_top = top - need_base;  // the fresh pages are taken now
     else

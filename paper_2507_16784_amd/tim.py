@@ -17,12 +17,12 @@ MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, MARK_CLOSE = 1, 2, 3, 4
 OUT_F32, OUT_BF16 = 0, 1
 PLAN_HDR, PLAN_TOTALS = 16, 8
 (HDR_SEQ, HDR_N, HDR_N_KEPT, HDR_FIRST_PRUNED, HDR_KEEP_PAGES, HDR_NEED, HDR_PAGE_OFF, HDR_PUSH, HDR_PUSH_OFF,
- HDR_BAD) = range(10)
-TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE = range(5)
+ HDR_BAD, HDR_EXT, HDR_EXT_OFF, HDR_EXT_TILE_OFF) = range(13)
+TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_TILES = range(7)
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_decode_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
+           "tim_decode_attn", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
 class tim_config(C.Structure):
@@ -64,6 +64,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_kv_compact": (C.c_int, [p, C.POINTER(tim_plan), i32, i32, p]),
         "tim_plan_commit": (C.c_int, [p, C.POINTER(tim_plan), p]),
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
+        "tim_extend_attn": (C.c_int, [p, i32, C.POINTER(tim_plan), p, p, i32, f32, i32, p]),
         "tim_pool_stats": (C.c_int, [p, p, p]),
         "tim_status": (C.c_int, [p, p]),
         "tim_timing_begin": (C.c_int, [p, i32]),
@@ -215,6 +216,15 @@ class Context:
         od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
         _check(lib().tim_decode_attn(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len, _stream()),
                "tim_decode_attn")
+
+    def tim_extend_attn(self, layer: int, plan: Plan, q_ext: torch.Tensor, out_ext: torch.Tensor, sm_scale: float):
+        assert q_ext.dtype == torch.bfloat16 and q_ext.is_cuda and q_ext.is_contiguous()
+        assert q_ext.dim() == 3 and tuple(q_ext.shape[1:]) == (self.cfg.q_heads, self.cfg.head_dim)
+        assert tuple(out_ext.shape) == tuple(q_ext.shape) and out_ext.is_cuda and out_ext.is_contiguous()
+        assert out_ext.dtype in (torch.float32, torch.bfloat16)
+        od = OUT_F32 if out_ext.dtype == torch.float32 else OUT_BF16
+        _check(lib().tim_extend_attn(self.handle, layer, C.byref(plan.c), _ptr(q_ext), _ptr(out_ext),
+                                     q_ext.shape[0], sm_scale, od, _stream()), "tim_extend_attn")
 
     def tim_pool_stats(self) -> torch.Tensor:
         out = torch.zeros(2, dtype=torch.int32, device=self.seq_len.device)

@@ -91,6 +91,12 @@ class GpuRuntime:
         self.ctx.tim_decode_attn(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
         return out.float().cpu().numpy()
 
+    def extend_attn(self, layer, plan, q_ext_bits, sm_scale, out_dtype=torch.float32):
+        q = self._bf16(q_ext_bits)
+        out = torch.zeros(q.shape, dtype=out_dtype, device=self.dev)
+        self.ctx.tim_extend_attn(layer, plan, q, out, sm_scale)
+        return out.float().cpu().numpy()
+
     # ---- read back ---------------------------------------------------------------------
     def state(self):
         c = self.ctx

@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from oracle.attention import attend
+from oracle.attention import attend, extend
 
 
 def _rand(t, hq=8, hkv=2, d=128, seed=0, scale=1.0):
@@ -86,3 +86,24 @@ def test_scale_matters_and_shift_of_scores_does_not():
     c = np.random.default_rng(12).standard_normal(128)
     k2 = k + c
     assert np.allclose(attend(q, k2, v, 0.1), a, atol=1e-10)
+
+
+def test_extend_equals_rows_of_dense_causal_attention():
+    # re-encoding positions f..T-1 attends exactly like rows f..T-1 of causal attention over the sequence
+    t, f, hq, hkv, d = 29, 11, 8, 2, 128
+    rng = np.random.default_rng(21)
+    qs = rng.standard_normal((t, hq, d))
+    k = rng.standard_normal((t, hkv, d))
+    v = rng.standard_normal((t, hkv, d))
+    sc = 1.0 / np.sqrt(d)
+    tq = torch.from_numpy(qs).permute(1, 0, 2)
+    tk = torch.from_numpy(k).permute(1, 0, 2).repeat_interleave(hq // hkv, 0)
+    tv = torch.from_numpy(v).permute(1, 0, 2).repeat_interleave(hq // hkv, 0)
+    dense = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=sc)
+    got = extend(qs[f:], k, v, f, sc)
+    assert np.allclose(got, dense[:, f:, :].permute(1, 0, 2).numpy(), atol=1e-12)
+    # the last extended token is ordinary decode attention over everything
+    assert np.allclose(got[-1], attend(qs[-1], k, v, sc), atol=1e-14)
+    # a token never sees later keys: changing them leaves earlier rows alone
+    k2 = k.copy(); k2[-1] += 5.0
+    assert np.array_equal(extend(qs[f:], k2, v, f, sc)[:-1], got[:-1])
