@@ -165,6 +165,72 @@ def cpu_baseline(shape, seed):
                 sample=f"{nseq} sequences x 1 layer of configuration 3: their big flush + {steps} decode steps")
 
 
+def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
+    """Every sequence takes its big flush in one call.  Reports the three flush calls and, on
+    the same plan, the extend attention (what re-encoding would add) for comparison."""
+    B = ctx.cfg.max_batch
+    ids = torch.arange(B, dtype=torch.int32, device="cuda")
+    ops = wl.step_ops(0)
+    reps = max(1, args.steps if args.steps < 16 else 3)
+
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); fn(); e1.record(); e1.synchronize()
+        return e0.elapsed_time(e1)
+
+    t_plan, t_compact, t_commit = [], [], []
+    for r in range(reps + 1):                       # first repetition is the warm-up
+        for n, t in initial.items():
+            getattr(ctx, n).copy_(t)
+        if ops:
+            ctx.tim_tree_mark(torch.tensor(ops, dtype=torch.int32, device="cuda").reshape(-1, 4))
+        torch.cuda.synchronize()
+        a = timed(lambda: ctx.tim_prune_plan(ids, shape.threshold, plan))
+        b = timed(lambda: ctx.tim_kv_compact(plan, 0, ctx.cfg.layers))
+        c = timed(lambda: ctx.tim_plan_commit(plan))
+        if r:
+            t_plan.append(a); t_compact.append(b); t_commit.append(c)
+    status = ctx.tim_status()
+    assert status == 0, f"device status {status}"
+    hdr = plan.hdr[:B].cpu().numpy().astype(np.int64)
+    tot = plan.totals.cpu().numpy()
+    moved = int(np.maximum(hdr[:, tim.HDR_N_KEPT] - hdr[:, tim.HDR_KEEP_PAGES] * 16, 0).sum())
+    n_before, n_after = int(hdr[:, tim.HDR_N].sum()), int(hdr[:, tim.HDR_N_KEPT].sum())
+    compact_bytes = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * ctx.cfg.layers
+    ms_c = float(np.median(t_compact))
+    # extend attention on the committed plan: every survivor behind the first pruned token re-attends
+    n_ext = int(tot[tim.TOT_EXT])
+    g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 2)
+    q_ext = (torch.randn(n_ext, shape.q_heads, 128, generator=g, device="cuda") * shape.kv_scale).to(torch.bfloat16)
+    out_ext = torch.empty_like(q_ext)
+    ctx.tim_extend_attn(0, plan, q_ext, out_ext, shape.q_scale)
+    t_ext = [timed(lambda: ctx.tim_extend_attn(l % ctx.cfg.layers, plan, q_ext, out_ext, shape.q_scale)) for l in range(4)]
+    f, m = hdr[:, tim.HDR_FIRST_PRUNED], hdr[:, tim.HDR_N_KEPT]
+    pairs = float(sum((int(mm) * (int(mm) + 1) - int(ff) * (int(ff) + 1)) // 2 for ff, mm in zip(f, m) if mm > ff))
+    ext_flops = pairs * shape.q_heads * 128 * 4.0                    # QK and PV, multiply + add, per layer
+    ms_e = float(np.median(t_ext))
+    res = {
+        "metric": "flush of all sequences at once: plan + KV compaction (RoPE re-rotation) + commit",
+        "value": round(float(np.median(t_plan)) + ms_c + float(np.median(t_commit)), 3), "unit": "ms per flush call",
+        "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name + "/all-big-flushes", "batch": B, "layers": ctx.cfg.layers,
+                   "tokens_before": n_before, "tokens_after": n_after, "prune_ratio": round(1 - n_after / n_before, 4),
+                   "moved_tokens": moved, "extended_tokens": n_ext},
+        "plan_ms": round(float(np.median(t_plan)), 3), "compact_ms": round(ms_c, 3),
+        "commit_ms": round(float(np.median(t_commit)), 3),
+        "roofline": {"bound": "hbm", "kernel": "tim_compact_kernel", "achieved": round(compact_bytes / (ms_c * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(compact_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "bytes_per_launch": compact_bytes},
+        "extend_attn": {"ms_per_layer": round(ms_e, 3), "ms_all_layers": round(ms_e * ctx.cfg.layers, 2),
+                        "roofline": {"bound": "mfma", "kernel": "tim_extend_attn_kernel",
+                                     "achieved": round(ext_flops / (ms_e * 1e-3) / 1e12, 1), "peak": 2500.0,
+                                     "unit": "TFLOP/s", "frac": round(ext_flops / (ms_e * 1e-3) / 1e12 / 2500.0, 4),
+                                     "flops_per_launch": ext_flops},
+                        "cost_vs_rerotation": round(ms_e * ctx.cfg.layers / ms_c, 1)},
+    }
+    print(json.dumps(res), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -175,6 +241,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dump", default="", help="write per-step lengths and attention timings to this .npz")
+    ap.add_argument("--mode", default="window", choices=["window", "flush"],
+                    help="window: the decode window (default, the headline number); flush: all big flushes in one "
+                         "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
@@ -201,7 +270,9 @@ def main():
     t_setup = time.perf_counter()
     shape, wl = configs.config3(batch=args.batch, steps=max(args.steps, args.warmup), seed=args.seed)
     shape.q_scale = 128 ** -0.5
-    ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=4096, layers_alloc=args.layers_alloc,
+    # all sequences flushing at once need all their fresh pages before any old page returns
+    headroom = 4096 if args.mode == "window" else 14336
+    ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=headroom, layers_alloc=args.layers_alloc,
                                  seed=args.seed)
     plan = tim.Plan(ctx.cfg, args.batch)
     B = args.batch
@@ -224,6 +295,9 @@ def main():
         staged["flush"].append(torch.tensor(ids, dtype=torch.int32, device="cuda") if ids else None)
     initial = {n: getattr(ctx, n).clone() for n in INT_STATE}
     torch.cuda.synchronize()
+    if args.mode == "flush":
+        flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args)
+        return
     log(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; warmup {args.warmup}, timing {args.steps} steps")
 
     run_steps(torch, tim, ctx, plan, shape, wl, staged, args.warmup, shape.layers, None)

@@ -5,7 +5,7 @@
 // K/V tile for 32 (token, head) query rows per wave and is bounded by the matrix cores
 // and L2 rather than by HBM.
 //
-// Decomposition.  grid = (tiles of 32 extended tokens, kv_heads).  A block's four waves
+// Decomposition.  grid = (kv_heads, tiles of 32 extended tokens).  A block's four waves
 // take 8 tokens each: two sets of 16 query rows (4 tokens x the 4 heads of the group).
 // Per pair of key pages a wave loads K and V exactly like the decode kernel and runs, per
 // set, S^T = K . Q^T (K tile as A operand, the 16 query rows as B columns) and
@@ -33,11 +33,15 @@ __device__ __forceinline__ uint32_t ex_pack_bf16(float lo, float hi) {
 __device__ __forceinline__ ex_bf16x8 ex_as_bf16x8(const uint4 &u) { return __builtin_bit_cast(ex_bf16x8, u); }
 
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(EX_THREADS)
+__global__ void __launch_bounds__(EX_THREADS, 2)
 tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer, const uint4 *__restrict__ q_ext,
                        void *__restrict__ out_ext, int n_ext_total, float scale_log2) {
-  const int tile = blockIdx.x, kvh = blockIdx.y;
-  if (!pl.totals[TIM_TOT_OK] || tile >= pl.totals[TIM_TOT_EXT_TILES]) return;
+  // workgroup ids run over the kv heads first: with 8 heads each XCD keeps one head's K/V in
+  // its L2 for all query tiles.  Tiles are taken last-first: under the causal mask the late
+  // tiles of a sequence are the long ones, and starting them first shortens the tail.
+  const int kvh = blockIdx.x;
+  if (!pl.totals[TIM_TOT_OK] || (int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
+  const int tile = pl.totals[TIM_TOT_EXT_TILES] - 1 - blockIdx.y;
   // flushed sequence of this tile: last e with EXT_TILE_OFF[e] <= tile (n_seqs is small)
   int lo = 0, hi = n_seqs - 1;
   while (lo < hi) {
@@ -225,7 +229,7 @@ extern "C" int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan
   if (!q_ext || !out_ext) return TIM_ERR_INVALID_ARG;
   // every sequence adds at most one partly filled tile
   const int tiles = (n_ext_total + EX_TILE_TOKENS - 1) / EX_TILE_TOKENS + plan->n_seqs;
-  dim3 grid(tiles, ctx->cfg.kv_heads);
+  dim3 grid(ctx->cfg.kv_heads, tiles);
   const float scale_log2 = sm_scale * 1.4426950408889634f;
   if (out_dtype == TIM_OUT_BF16)
     hipLaunchKernelGGL((tim_extend_attn_kernel<true>), grid, dim3(EX_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
