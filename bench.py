@@ -85,10 +85,10 @@ def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed):
 
 
 INT_STATE = ("page_table", "seq_len", "free_stack", "free_top", "status", "node_tok_begin", "node_sub_begin",
-             "node_sub_end", "node_tok_end", "node_list_order", "n_nodes", "lists_done")
+             "node_sub_end", "node_tok_end", "node_list_order", "n_nodes", "lists_done", "keep_mask")
 
 
-def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, record):
+def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, record, flush_kind="compact"):
     """Launches n_steps steps.  `record` (or None) collects events and length logs."""
     L_alloc = ctx.cfg.layers
     B = ctx.cfg.max_batch
@@ -98,8 +98,10 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
         ops = staged["ops"][step]
         if ops is not None:
             ctx.tim_tree_mark(ops)
-        ids = staged["flush"][step]
-        if ids is not None:
+        ids = staged["flush"][step] if flush_kind != "none" else None
+        if ids is not None and flush_kind == "mask":       # in-forward variant: hide, move nothing
+            ctx.tim_prune_mask(ids, shape.threshold, plan)
+        elif ids is not None:
             ctx.tim_prune_plan(ids, shape.threshold, plan)
             reps = (layers_run + L_alloc - 1) // L_alloc
             for r in range(reps):                    # reps == 1 unless the pool had to be aliased
@@ -118,7 +120,10 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
         for layer in range(layers_run):
             la = layer % L_alloc
             ctx.tim_kv_append(la, staged["k_new"][layer], staged["v_new"][layer])
-            ctx.tim_decode_attn(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
+            if flush_kind == "mask":
+                ctx.tim_decode_attn_masked(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
+            else:
+                ctx.tim_decode_attn(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
         host = staged["pinned"][step % len(staged["pinned"])]
         host.copy_(ctx.seq_len, non_blocking=True)
         ev = torch.cuda.Event()
@@ -231,6 +236,45 @@ def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
     print(json.dumps(res), flush=True)
 
 
+def sweep_mode(torch, tim, np, ctx, plan, shape, wl, staged, initial, args):
+    """Synthetic analogue of the paper's throughput-vs-pruning-buffer figure: the same window
+    with thresholds 0/1/2/4 under flush-by-compaction and under in-forward masking, and
+    without any pruning."""
+    B = ctx.cfg.max_batch
+    rows = []
+    variants = [("none", 0)] + [("compact", t) for t in (0, 1, 2, 4)] + [("mask", t) for t in (0, 1, 2, 4)]
+    for kind, thr in variants:
+        for n, t in initial.items():
+            getattr(ctx, n).copy_(t)
+        shape.threshold = thr
+        lens = torch.zeros(args.steps, B, dtype=torch.int32, device="cuda")
+        record = dict(hdr=[], lens=lens)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, record, flush_kind=kind)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        status = ctx.tim_status()
+        assert status == 0, f"device status {status}"
+        vis = None
+        if kind == "mask":           # visible tokens at the end of the window
+            w = ctx.keep_mask.cpu().numpy().view(np.uint32)
+            bits = ((w[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(B, -1)
+            end = lens[-1].cpu().numpy()
+            vis = float(np.mean([bits[b, : end[b]].sum() for b in range(B)]))
+        rows.append({"flush": kind, "threshold": None if kind == "none" else thr,
+                     "steps_per_s": round(args.steps / dt, 2), "tokens_per_s": round(args.steps / dt * B, 1),
+                     "mean_positions_in_use_at_end": round(float(lens[-1].float().mean()), 1),
+                     "mean_visible_tokens_at_end": None if vis is None else round(vis, 1)})
+        log(f"[sweep] {rows[-1]}")
+    base = rows[0]["steps_per_s"]
+    for r in rows:
+        r["vs_no_pruning"] = round(r["steps_per_s"] / base, 3)
+    print(json.dumps({"metric": "decode steps/s by pruning-buffer threshold and flush variant", "unit": "decode steps/s",
+                      "n_gpus": 1, "steps": args.steps, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": shape.name, "batch": B, "layers": shape.layers}, "sweep": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -241,9 +285,11 @@ def main():
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dump", default="", help="write per-step lengths and attention timings to this .npz")
-    ap.add_argument("--mode", default="window", choices=["window", "flush"],
+    ap.add_argument("--mode", default="window", choices=["window", "flush", "sweep"],
                     help="window: the decode window (default, the headline number); flush: all big flushes in one "
-                         "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan")
+                         "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan; "
+                         "sweep: the window for pruning-buffer thresholds 0/1/2/4, without pruning, and with the "
+                         "in-forward (masking) variant")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
@@ -297,6 +343,9 @@ def main():
     torch.cuda.synchronize()
     if args.mode == "flush":
         flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args)
+        return
+    if args.mode == "sweep":
+        sweep_mode(torch, tim, np, ctx, plan, shape, wl, staged, initial, args)
         return
     log(f"[bench] setup {time.perf_counter() - t_setup:.1f} s; warmup {args.warmup}, timing {args.steps} steps")
 

@@ -104,6 +104,8 @@ typedef struct {
   int32_t *lists_done;       /* device [max_batch], lists completed so far */
   float *attn_ws;            /* device scratch for split partials, see tim_attn_ws_bytes */
   int64_t attn_ws_bytes;
+  uint32_t *keep_mask;       /* device [max_batch][ceil(max_pages_per_seq / 2)], bit t%32 of word t/32 = token t is
+                                visible; only the *_mask calls use it, may be NULL otherwise */
 } tim_state;
 
 /*
@@ -260,6 +262,22 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
  */
 int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan, const void *q_ext, void *out_ext,
                     int32_t n_ext_total, float sm_scale, int32_t out_dtype, tim_stream stream);
+
+/*
+ * In-forward variant (Sec. 3.1 mentions it and rejects it as slower; Sec. 4.3's "80 % line"):
+ * instead of moving anything, the tokens of the evicted lists are made invisible in
+ * tim_state.keep_mask and tim_decode_attn_masked skips them inside attention: pages with no
+ * visible token are not read, others are read in full and masked.  Positions, lengths,
+ * page tables and node coordinates do not change, so positional slots are NOT reused: this
+ * is the trade-off the paper's runtime avoids, kept here to measure it.  A context uses
+ * either the flush calls or the mask calls, not both.  tim_pool_reset makes every token
+ * visible.  The rule and the arguments are those of tim_prune_plan; `plan` only lends its
+ * cover/new_pos scratch.
+ */
+int tim_prune_mask(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t threshold, tim_plan *plan,
+                   tim_stream stream);
+int tim_decode_attn_masked(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
+                           int32_t max_seq_len, tim_stream stream);
 
 /* out: device int32 [2] = (free pages, pages referenced by page tables). */
 int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream);

@@ -74,6 +74,8 @@ class OracleRuntime:
         self.lists_done = np.zeros(c.max_batch, dtype=np.int32)
         self.threshold = threshold
         self.buffers = [PruningBuffer(threshold) for _ in range(c.max_batch)]
+        # in-forward variant only: visibility of every logical token (nothing is ever moved)
+        self.visible = np.ones((c.max_batch, c.max_pages_per_seq * c.page_size), dtype=bool)
 
     # ---- helpers -------------------------------------------------------
     def _pages_of(self, n_tokens: int) -> int:
@@ -218,6 +220,27 @@ class OracleRuntime:
         for b in range(c.max_batch):
             kb, vb = self.gather_kv(layer, b)
             out[b] = attend(bf16.to_f64(q[b]), bf16.to_f64(kb), bf16.to_f64(vb), scale)
+        return out
+
+    # ---- in-forward variant: hide instead of move -------------------------------------------
+    def prune_mask(self, seq_ids) -> None:
+        """The lists that left the buffer become invisible; positions, pages and node
+        coordinates stay as they are (Sec. 3.1's alternative that the paper's runtime avoids)."""
+        for b in sorted(seq_ids):
+            n = int(self.seq_len[b])
+            for i in self.buffers[b].take_pending():
+                sb, se = int(self.sub_begin[b, i]), int(self.sub_end[b, i])
+                if sb < 0 or se < sb or se > n:
+                    raise ValueError("bad range")
+                self.visible[b, sb:se] = False
+
+    def decode_attn_masked(self, layer: int, q: np.ndarray, scale: float) -> np.ndarray:
+        c = self.cfg
+        out = np.empty((c.max_batch, c.q_heads, c.head_dim), dtype=np.float32)
+        for b in range(c.max_batch):
+            kb, vb = self.gather_kv(layer, b)
+            keep = self.visible[b, : int(self.seq_len[b])]
+            out[b] = attend(bf16.to_f64(q[b]), bf16.to_f64(kb[keep]), bf16.to_f64(vb[keep]), scale)
         return out
 
     def extend_attn(self, layer: int, ev: EventPlan, q_ext: np.ndarray, scale: float) -> np.ndarray:

@@ -254,7 +254,7 @@ __device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __bui
 
 #define AT_LAZY_MAX 8.0f
 
-template <bool OUT_BF16>
+template <bool OUT_BF16, bool MASKED>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
                              void *__restrict__ out, float scale_log2, int cpb) {
@@ -299,6 +299,13 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     const int my_pid = ptab[min(pg0 + (lane & (AT_PAGES_PER_WAVE - 1)), max(n_pages - 1, 0))];
     for (int pg = pg0; pg < pg1; pg += 2) {
       const bool has_b = pg + 1 < pg1;
+      // in-forward variant: visibility of the pair's 32 tokens (pairs start at even pages);
+      // a pair without a visible token is not read at all
+      uint32_t vis = 0xffffffffu;
+      if (MASKED) {
+        vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * ((cfg.max_pages_per_seq + 1) / 2) + (pg >> 1)]);
+        if (vis == 0) continue;
+      }
       int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
       int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
       if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
@@ -320,7 +327,7 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
       const int left_a = n - pg * TIM_PS;
       const int left_b = has_b ? n - (pg + 1) * TIM_PS : 0;
-      const bool full = left_b >= TIM_PS;  // then page A is full as well
+      const bool full = left_b >= TIM_PS && vis == 0xffffffffu;  // then page A is full as well
 
       at_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -338,7 +345,8 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const bool ok_a = 4 * g + r < left_a, ok_b = 4 * g + r < left_b;
+          const bool ok_a = 4 * g + r < left_a && ((vis >> (4 * g + r)) & 1u);
+          const bool ok_b = 4 * g + r < left_b && ((vis >> (16 + 4 * g + r)) & 1u);
           // the select is on the product: a stale row may hold anything, also NaN or Inf
           t[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
           t[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
@@ -476,10 +484,12 @@ extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
   return (int64_t)cfg->max_batch * cfg->q_heads * AT_MAX_SLOTS * (TIM_D + 2) * (int64_t)sizeof(float);
 }
 
-template <bool MFMA, bool OUT_BF16>
+template <int IMPL, bool OUT_BF16>  // 0 = vector ALU, 1 = matrix cores, 2 = matrix cores with visibility mask
 static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
                       float scale_log2, int cpb) {
-  auto kernel = MFMA ? tim_attn_partial_mfma_kernel<OUT_BF16> : tim_attn_partial_kernel<OUT_BF16>;
+  auto kernel = IMPL == 2   ? tim_attn_partial_mfma_kernel<OUT_BF16, true>
+                : IMPL == 1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false>
+                            : tim_attn_partial_kernel<OUT_BF16>;
   const uint4 *q4 = reinterpret_cast<const uint4 *>(q);
   if (ctx->timing_on && ctx->timing_n < (int)ctx->ev_start.size()) {
     // events attached to the dispatch itself: the kernel's own begin/end, no extra barrier
@@ -524,10 +534,10 @@ extern "C" int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out) {
   return rc;
 }
 
-extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
-                               int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
+static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
+                     int32_t max_seq_len, tim_stream stream, bool masked) {
   if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers ||
-      (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0)
+      (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask))
     return TIM_ERR_INVALID_ARG;
   const tim_config &cfg = ctx->cfg;
   const int full = cfg.max_pages_per_seq * TIM_PS;
@@ -548,12 +558,15 @@ extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void 
   hipStream_t s = tim_hs(stream);
   dim3 grid(cfg.max_batch * cfg.kv_heads, slots);
   const bool bf = out_dtype == TIM_OUT_BF16;
-  if (ctx->attn_impl == 1) {
-    if (bf) at_launch<true, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
-    else at_launch<true, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+  if (masked) {
+    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+  } else if (ctx->attn_impl == 1) {
+    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
   } else {
-    if (bf) at_launch<false, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
-    else at_launch<false, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
   }
   TIM_LAUNCH_CHECK();
   if (slots > 1) {  // with one slot every block has already written its final output
@@ -563,4 +576,14 @@ extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void 
     TIM_LAUNCH_CHECK();
   }
   return TIM_OK;
+}
+
+extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
+                               int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
+  return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, false);
+}
+
+extern "C" int tim_decode_attn_masked(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
+                                      int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
+  return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, true);
 }

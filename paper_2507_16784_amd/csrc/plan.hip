@@ -246,6 +246,82 @@ __global__ void tim_plan_commit_kernel(tim_config cfg, tim_state st, tim_plan pl
   if (e == 0 && i == 0) *st.free_top = pl.totals[TIM_TOT_TOP_AFTER_POP] + pl.totals[TIM_TOT_PUSH];
 }
 
+// In-forward variant: same rule, but the evicted tokens are only made invisible.  One block
+// per sequence: difference array -> coverage by a block scan -> one visibility flag per
+// token in scratch -> packed 32 per word and AND-ed into the persistent mask.
+__global__ void __launch_bounds__(PLAN_THREADS)
+tim_prune_mask_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *__restrict__ seq_ids, int threshold) {
+  __shared__ int smem[17];
+  __shared__ int s_bad;
+  const int e = blockIdx.x, tid = threadIdx.x;
+  const int b = seq_ids[e];
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  if (b < 0 || b >= cfg.max_batch || (e > 0 && seq_ids[e - 1] >= b)) {
+    if (tid == 0) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+    return;
+  }
+  const int T = cfg.max_pages_per_seq * TIM_PS;
+  const int n = st.seq_len[b];
+  int32_t *cover = pl.cover + (int64_t)e * (T + 1);
+  int32_t *vis = pl.new_pos + (int64_t)e * T;
+  for (int t = tid; t <= n; t += PLAN_THREADS) cover[t] = 0;
+  __syncthreads();
+  const int64_t row = (int64_t)b * cfg.max_nodes;
+  const int nn = min(st.n_nodes[b], cfg.max_nodes);
+  const int gone_below = st.lists_done[b] - threshold;
+  for (int i = tid; i < nn; i += PLAN_THREADS) {
+    const int lo = st.node_list_order[row + i];
+    if (lo < 0 || lo >= gone_below) continue;
+    const int sb = st.node_sub_begin[row + i], se = st.node_sub_end[row + i];
+    if (sb < 0 || se < sb || se > n) {
+      atomicOr(&s_bad, 1);
+      continue;
+    }
+    if (se > sb) {
+      atomicAdd(&cover[sb], 1);
+      atomicAdd(&cover[se], -1);
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
+  if (s_bad) {
+    if (tid == 0) tim_set_status(st.status, TIM_ERR_BAD_TREE);
+    return;
+  }
+  int cov_base = 0;
+  for (int t0 = 0; t0 < n; t0 += PLAN_THREADS * PLAN_ITEMS) {
+    const int tb = t0 + tid * PLAN_ITEMS;
+    int c[PLAN_ITEMS];
+    int csum = 0;
+#pragma unroll
+    for (int k = 0; k < PLAN_ITEMS; ++k) {
+      c[k] = (tb + k < n) ? cover[tb + k] : 0;
+      csum += c[k];
+    }
+    int ctot;
+    int cexcl = tim_block_incl_scan(csum, smem, &ctot) - csum + cov_base;
+#pragma unroll
+    for (int k = 0; k < PLAN_ITEMS; ++k) {
+      cexcl += c[k];
+      if (tb + k < n) vis[tb + k] = cexcl == 0 ? 1 : 0;
+    }
+    cov_base += ctot;
+  }
+  __threadfence_block();
+  __syncthreads();
+  const int words = (n + 31) / 32;
+  uint32_t *mask = st.keep_mask + (int64_t)b * ((cfg.max_pages_per_seq + 1) / 2);
+  for (int w = tid; w < words; w += PLAN_THREADS) {
+    uint32_t bits = 0;
+    for (int k = 0; k < 32; ++k) {
+      const int t = 32 * w + k;
+      if (t >= n || vis[t]) bits |= 1u << k;  // tokens not decoded yet stay visible
+    }
+    mask[w] &= bits;
+  }
+}
+
 static int plan_ok(const tim_ctx *ctx, const tim_plan *p) {
   return ctx && ctx->bound && p && p->seq_ids && p->cover && p->rank && p->kept_idx && p->new_pos && p->delta &&
          p->src_slot && p->dst_slot && p->new_table && p->hdr && p->totals;
@@ -275,6 +351,17 @@ extern "C" int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream st
   const int span = ctx->cfg.max_pages_per_seq > ctx->cfg.max_nodes ? ctx->cfg.max_pages_per_seq : ctx->cfg.max_nodes;
   hipLaunchKernelGGL(tim_plan_commit_kernel, dim3((span + 255) / 256, plan->n_seqs), dim3(256), 0, tim_hs(stream),
                      ctx->cfg, ctx->st, *plan);
+  TIM_LAUNCH_CHECK();
+  return TIM_OK;
+}
+
+extern "C" int tim_prune_mask(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t threshold, tim_plan *plan,
+                              tim_stream stream) {
+  if (!ctx || !ctx->bound || !ctx->st.keep_mask || !plan || !plan->cover || !plan->new_pos || !seq_ids || n_seqs <= 0 ||
+      n_seqs > plan->max_seqs || n_seqs > ctx->cfg.max_batch || threshold < 0)
+    return TIM_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(tim_prune_mask_kernel, dim3(n_seqs), dim3(PLAN_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
+                     seq_ids, threshold);
   TIM_LAUNCH_CHECK();
   return TIM_OK;
 }

@@ -17,6 +17,10 @@ __global__ void tim_reset_kernel(tim_config cfg, tim_state st) {
     st.node_tok_end[k] = -1;
     st.node_list_order[k] = -1;
   }
+  if (st.keep_mask) {
+    const int64_t nw = (int64_t)cfg.max_batch * ((cfg.max_pages_per_seq + 1) / 2);
+    for (int64_t k = i; k < nw; k += stride) st.keep_mask[k] = 0xffffffffu;
+  }
   for (int64_t k = i; k < cfg.max_batch; k += stride) {
     st.seq_len[k] = 0;
     st.n_nodes[k] = 0;

@@ -22,7 +22,7 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_decode_attn", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
+           "tim_decode_attn", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
 class tim_config(C.Structure):
@@ -34,7 +34,7 @@ class tim_state(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("k_pool", "v_pool", "page_table", "seq_len", "free_stack", "free_top",
                                           "status", "node_tok_begin", "node_sub_begin", "node_sub_end",
                                           "node_tok_end", "node_list_order", "n_nodes", "lists_done", "attn_ws")] + \
-               [("attn_ws_bytes", C.c_int64)]
+               [("attn_ws_bytes", C.c_int64), ("keep_mask", C.c_void_p)]
 
 
 _PLAN_PTRS = ("seq_ids", "cover", "rank", "kept_idx", "new_pos", "delta", "src_slot", "dst_slot", "new_table",
@@ -64,6 +64,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_kv_compact": (C.c_int, [p, C.POINTER(tim_plan), i32, i32, p]),
         "tim_plan_commit": (C.c_int, [p, C.POINTER(tim_plan), p]),
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
+        "tim_decode_attn_masked": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
+        "tim_prune_mask": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
         "tim_extend_attn": (C.c_int, [p, i32, C.POINTER(tim_plan), p, p, i32, f32, i32, p]),
         "tim_pool_stats": (C.c_int, [p, p, p]),
         "tim_status": (C.c_int, [p, p]),
@@ -157,6 +159,7 @@ class Context:
         self.node_list_order = torch.full((max_batch, max_nodes), -1, **i32)
         self.n_nodes = torch.zeros(max_batch, **i32)
         self.lists_done = torch.zeros(max_batch, **i32)
+        self.keep_mask = torch.full((max_batch, (max_pages_per_seq + 1) // 2), -1, **i32)   # all bits set
         ws_bytes = lib().tim_attn_ws_bytes(C.byref(self.cfg))
         self.attn_ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=device)
         self.state = tim_state(
@@ -164,7 +167,7 @@ class Context:
                                                         "free_top", "status", "node_tok_begin", "node_sub_begin",
                                                         "node_sub_end", "node_tok_end", "node_list_order", "n_nodes",
                                                         "lists_done", "attn_ws")},
-            attn_ws_bytes=ws_bytes)
+            attn_ws_bytes=ws_bytes, keep_mask=self.keep_mask.data_ptr())
         _check(lib().tim_bind(self.handle, C.byref(self.state)), "tim_bind")
         self.tim_pool_reset()
 
@@ -216,6 +219,20 @@ class Context:
         od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
         _check(lib().tim_decode_attn(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len, _stream()),
                "tim_decode_attn")
+
+    def tim_prune_mask(self, seq_ids: torch.Tensor, threshold: int, plan: Plan):
+        assert seq_ids.dtype == torch.int32 and seq_ids.is_cuda and seq_ids.is_contiguous()
+        _check(lib().tim_prune_mask(self.handle, _ptr(seq_ids), seq_ids.shape[0], threshold, C.byref(plan.c),
+                                    _stream()), "tim_prune_mask")
+
+    def tim_decode_attn_masked(self, layer: int, q: torch.Tensor, out: torch.Tensor, sm_scale: float,
+                               max_seq_len: int = 0):
+        assert q.dtype == torch.bfloat16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim) == tuple(out.shape)
+        assert out.is_cuda and out.is_contiguous() and out.dtype in (torch.float32, torch.bfloat16)
+        od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+        _check(lib().tim_decode_attn_masked(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len,
+                                            _stream()), "tim_decode_attn_masked")
 
     def tim_extend_attn(self, layer: int, plan: Plan, q_ext: torch.Tensor, out_ext: torch.Tensor, sm_scale: float):
         assert q_ext.dtype == torch.bfloat16 and q_ext.is_cuda and q_ext.is_contiguous()

@@ -91,6 +91,20 @@ class GpuRuntime:
         self.ctx.tim_decode_attn(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
         return out.float().cpu().numpy()
 
+    def prune_mask(self, seq_ids):
+        self.ctx.tim_prune_mask(self._i32(sorted(seq_ids)), self.threshold, self.plan)
+
+    def decode_attn_masked(self, layer, q_bits, sm_scale, out_dtype=torch.float32):
+        out = torch.empty((self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim), dtype=out_dtype, device=self.dev)
+        self.ctx.tim_decode_attn_masked(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
+        return out.float().cpu().numpy()
+
+    def visible(self):
+        """keep_mask unpacked to one bool per logical token: [B, T]."""
+        w = self.ctx.keep_mask.cpu().numpy().view(np.uint32)
+        bits = (w[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
+        return bits.reshape(w.shape[0], -1).astype(bool)
+
     def extend_attn(self, layer, plan, q_ext_bits, sm_scale, out_dtype=torch.float32):
         q = self._bf16(q_ext_bits)
         out = torch.zeros(q.shape, dtype=out_dtype, device=self.dev)

@@ -361,3 +361,38 @@ def test_extend_attention_after_flush(gb, case):
         for e, r in rows:
             assert np.allclose(dec[e], got[r], atol=1e-2 * np.abs(got[r]).max() + 1e-6)
         assert gpu.status() == 0
+
+
+@pytest.mark.parametrize("threshold,cadence,spec_name", [(0, 4, "tiny"), (2, 9, "tiny"), (1, 16, "c1")])
+def test_in_forward_masked_variant(gb, threshold, cadence, spec_name):
+    """The no-compaction variant: evicted lists only become invisible.  The visibility mask is
+    compared bit for bit, attention over the visible tokens within the attention bars, and
+    lengths / page tables / node coordinates must not move at all."""
+    if spec_name == "tiny":
+        seeds, p0s, steps, spec = [61, 62, 63], [90, 17, 260], 70, SPEC_TINY
+    else:
+        seeds, p0s, steps, spec = [64, 65], [3000, 1111], 48, SPEC_C1
+    traces = [generate(s, p + steps + 1, spec) for s, p in zip(seeds, p0s)]
+    nseq = len(seeds)
+    wl = Workload(traces, p0s, steps, every(cadence, steps, nseq))
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=12)
+    ora = OracleRuntime(cfg, threshold)
+    harness.preload_oracle(ora, wl, 4, 1.0)
+    gpu = gb.GpuRuntime(cfg, threshold)
+    gb.preload_gpu(gpu, wl, 4, 1.0)
+    hidden = 0
+    for step in range(steps):
+        ops = wl.step_ops(step)
+        if ops:
+            ora.mark(ops); gpu.mark(ops)
+        if wl.flush_seqs(step):
+            ora.prune_mask(range(nseq)); gpu.prune_mask(range(nseq))
+            assert np.array_equal(gpu.visible()[:, : ora.visible.shape[1]], ora.visible)
+        ora.advance(); gpu.advance()
+        q, k, v = harness.step_inputs(4, step, cfg, 1.0)
+        ora.append(0, k[0], v[0]); gpu.append(0, k[0], v[0])
+        check_attention(gpu.decode_attn_masked(0, q[0], 128 ** -0.5), ora.decode_attn_masked(0, q[0], 128 ** -0.5))
+        check_state(ora, gpu)
+        hidden = int((~ora.visible).sum())
+    assert gpu.status() == 0 and hidden > 0
+    assert list(ora.seq_len) == [p + steps for p in p0s]             # nothing was moved or shortened

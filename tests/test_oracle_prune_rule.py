@@ -266,3 +266,29 @@ def test_replay_survivors_match_brute_force_in_absolute_coordinates(threshold, c
             rt.append(0, vnew, vnew)
         if threshold >= 10**6:
             assert rt.seq_len[0] == p0 + steps                  # nothing is ever pruned
+
+
+@pytest.mark.parametrize("threshold", [0, 1, 2])
+def test_mask_variant_hides_exactly_the_tokens_the_flush_would_drop(threshold):
+    """In-forward variant: the visible set, in unchanged coordinates, equals the brute-force
+    statement of the rule, and lengths never shrink."""
+    spec = TreeSpec(depth_max=4, branch=(1, 3), thought=(2, 9), concl=(1, 4), prompt_len=5)
+    for seed in range(4):
+        tr = generate(seed + 100, 300, spec)
+        p0, steps = 30, 250
+        wl = Workload([tr], [p0], steps, every(3, steps, 1))
+        cfg = harness.make_config(wl, 1, 4, 1, headroom_pages=20)
+        rt = OracleRuntime(cfg, threshold)
+        harness.preload_oracle(rt, wl, seed, 1.0)
+        last = -1
+        for step in range(steps):
+            ops = wl.step_ops(step)
+            if ops:
+                rt.mark(ops)
+            if wl.flush_seqs(step):
+                rt.prune_mask([0])
+                last = p0 + step
+                want = _survivors_brute_force(tr, p0 + step, threshold, last)
+                assert list(np.flatnonzero(rt.visible[0, : p0 + step])) == want
+            assert rt.advance() == 0
+        assert rt.seq_len[0] == p0 + steps
