@@ -196,6 +196,25 @@ int tim_tree_mark(tim_ctx *ctx, const int32_t *ops, int32_t n_ops, tim_stream st
 int tim_seq_advance(tim_ctx *ctx, tim_stream stream);
 
 /*
+ * Bulk form of tim_seq_advance for tool responses, which the runtime encodes as a batch of
+ * new tokens that extend the cache (Sec. 2.1 "tooluse", Sec. 3.2): sequence b grows by
+ * counts[b] >= 0 tokens.  New pages are popped in ascending (sequence, logical page) order;
+ * if the pool or a page table cannot take the whole batch nothing changes and status is set.
+ * counts: device int32 [max_batch].
+ */
+int tim_seq_extend(tim_ctx *ctx, const int32_t *counts, tim_stream stream);
+
+/*
+ * Writes the keys and values of the last counts[b] tokens of every sequence for one layer
+ * (positions seq_len[b]-counts[b] .. seq_len[b]-1, i.e. right after tim_seq_extend).
+ * k_rows, v_rows: device bf16 [n_rows][kv_heads][128], sequences in ascending order, keys
+ * rotated at their positions.  row_off: device int32 [max_batch + 1], exclusive prefix sum of
+ * counts (row_off[max_batch] = n_rows); n_rows is the host's copy of that total.
+ */
+int tim_kv_write(tim_ctx *ctx, int32_t layer, const int32_t *row_off, int32_t n_rows, const void *k_rows,
+                 const void *v_rows, tim_stream stream);
+
+/*
  * Writes the pending token's key and value of one layer into slot seq_len-1 of
  * every sequence.  k_new, v_new: device bf16 [max_batch][kv_heads][128]; the key
  * is already rotated at position seq_len-1.

@@ -131,6 +131,39 @@ class OracleRuntime:
         self.seq_len += 1
         return OK
 
+    def extend_seq(self, counts) -> int:
+        """Bulk form of advance(): a tool response enters the cache as a batch of new tokens
+        (paper Sec. 2.1 "tooluse", Sec. 3.2).  Pages pop in ascending (sequence, page) order."""
+        c = self.cfg
+        if any(int(x) < 0 for x in counts):
+            self.status = self.status or -1
+            return -1
+        have = [self._pages_of(int(n)) for n in self.seq_len]
+        want = [self._pages_of(int(n) + int(x)) for n, x in zip(self.seq_len, counts)]
+        if any(w > c.max_pages_per_seq for w in want):
+            self.status = self.status or ERR_SEQ_TOO_LONG
+            return ERR_SEQ_TOO_LONG
+        if sum(w - h for w, h in zip(want, have)) > self.free.top:
+            self.status = self.status or ERR_OOM_PAGES
+            return ERR_OOM_PAGES
+        for b in range(c.max_batch):
+            for p in range(have[b], want[b]):
+                self.page_table[b, p] = self.free.pop()
+            self.seq_len[b] += int(counts[b])
+        return OK
+
+    def write_rows(self, layer: int, counts, k_rows: np.ndarray, v_rows: np.ndarray) -> None:
+        """k_rows/v_rows: bf16 bits [sum(counts), Hkv, D], sequences ascending; they become the
+        last counts[b] tokens of each sequence."""
+        at = 0
+        for b in range(self.cfg.max_batch):
+            n, cb = int(self.seq_len[b]), int(counts[b])
+            if cb:
+                s = self.slots_of(b, np.arange(n - cb, n))
+                self.k[layer, s] = k_rows[at : at + cb]
+                self.v[layer, s] = v_rows[at : at + cb]
+            at += cb
+
     def append(self, layer: int, k_new: np.ndarray, v_new: np.ndarray) -> None:
         """k_new/v_new: bf16 bits [B, Hkv, D]; K already carries its position."""
         for b in range(self.cfg.max_batch):

@@ -124,6 +124,93 @@ __global__ void __launch_bounds__(1024) tim_advance_kernel(tim_config cfg, tim_s
   if (tid == 0) *st.free_top = top - total;
 }
 
+// ---- reserve several slots per sequence (tool responses) --------------------------------
+// Single block, same deterministic pop order as the one-token case: sequence b needs
+// ceil((n+c)/16) - ceil(n/16) pages; an exclusive scan gives its first depth below the top.
+__global__ void __launch_bounds__(1024) tim_extend_kernel(tim_config cfg, tim_state st, const int32_t *__restrict__ counts) {
+  __shared__ int smem[17];
+  __shared__ int s_bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  const int top = *st.free_top;
+  int cnt = 0;
+  for (int b = tid; b < cfg.max_batch; b += blockDim.x) {
+    const int n = st.seq_len[b], c = counts[b];
+    if (c < 0) {
+      atomicOr(&s_bad, 2);
+      continue;
+    }
+    const int have = (n + TIM_PS - 1) / TIM_PS, want = (n + c + TIM_PS - 1) / TIM_PS;
+    if (want > cfg.max_pages_per_seq) atomicOr(&s_bad, 1);
+    cnt += want - have;
+  }
+  int total;
+  tim_block_incl_scan(cnt, smem, &total);
+  __syncthreads();
+  if (s_bad) {
+    if (tid == 0) tim_set_status(st.status, (s_bad & 2) ? TIM_ERR_INVALID_ARG : TIM_ERR_SEQ_TOO_LONG);
+    return;
+  }
+  if (total > top) {
+    if (tid == 0) tim_set_status(st.status, TIM_ERR_OOM_PAGES);
+    return;
+  }
+  int base = 0;
+  for (int b0 = 0; b0 < cfg.max_batch; b0 += blockDim.x) {
+    const int b = b0 + tid;
+    int need = 0, n = 0, c = 0, have = 0;
+    if (b < cfg.max_batch) {
+      n = st.seq_len[b];
+      c = counts[b];
+      have = (n + TIM_PS - 1) / TIM_PS;
+      need = (n + c + TIM_PS - 1) / TIM_PS - have;
+    }
+    int chunk_total;
+    const int incl = tim_block_incl_scan(need, smem, &chunk_total);
+    if (b < cfg.max_batch) {
+      const int first = base + incl - need;
+      for (int k = 0; k < need; ++k)
+        st.page_table[(int64_t)b * cfg.max_pages_per_seq + have + k] = st.free_stack[top - 1 - (first + k)];
+      st.seq_len[b] = n + c;
+    }
+    base += chunk_total;
+  }
+  if (tid == 0) *st.free_top = top - total;
+}
+
+// ---- write the rows of the tokens just reserved ---------------------------------------------
+// One thread moves 16 bytes of one (row, kv head) of K or V; the row's sequence is found by
+// bisection in the prefix sums.
+__global__ void tim_write_rows_kernel(tim_config cfg, tim_state st, int layer, const int32_t *__restrict__ row_off,
+                                      int n_rows, const uint4 *__restrict__ k_rows, const uint4 *__restrict__ v_rows) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over n_rows * Hkv * 16 * 2
+  const int64_t per = (int64_t)n_rows * cfg.kv_heads * 16;
+  if (idx >= 2 * per) return;
+  const int which = (int)(idx / per);
+  const int64_t r = idx % per;
+  const int piece = (int)(r % 16);
+  const int h = (int)((r / 16) % cfg.kv_heads);
+  const int row = (int)(r / (16 * cfg.kv_heads));
+  int lo = 0, hi = cfg.max_batch - 1;  // last b with row_off[b] <= row
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (row_off[mid] <= row) lo = mid; else hi = mid - 1;
+  }
+  const int b = lo, c = row_off[b + 1] - row_off[b];
+  const int t = st.seq_len[b] - c + (row - row_off[b]);
+  if (row >= row_off[cfg.max_batch] || t < 0) return;
+  const int page = st.page_table[(int64_t)b * cfg.max_pages_per_seq + t / TIM_PS];
+  if (page < 0 || page >= cfg.num_pages) {
+    tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+    return;
+  }
+  const int64_t tile = ((int64_t)layer * cfg.num_pages + page) * cfg.kv_heads + h;
+  uint4 *pool = reinterpret_cast<uint4 *>(which ? st.v_pool : st.k_pool);
+  const uint4 *src = which ? v_rows : k_rows;
+  pool[tile * (TIM_TILE_BYTES / 16) + (t % TIM_PS) * 16 + piece] = src[((int64_t)row * cfg.kv_heads + h) * 16 + piece];
+}
+
 // ---- append the pending token's K/V row of one layer ------------------------------------
 // One thread moves 16 bytes; 16 threads cover a 256-byte row; K and V rows of all
 // (sequence, kv head) pairs are spread over the grid.
@@ -187,6 +274,29 @@ extern "C" int tim_seq_advance(tim_ctx *ctx, tim_stream stream) {
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
   hipLaunchKernelGGL(tim_advance_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st);
+  TIM_LAUNCH_CHECK();
+  return TIM_OK;
+}
+
+extern "C" int tim_seq_extend(tim_ctx *ctx, const int32_t *counts, tim_stream stream) {
+  if (!ctx || !ctx->bound || !counts) return TIM_ERR_INVALID_ARG;
+  int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
+  if (threads > 1024) threads = 1024;
+  hipLaunchKernelGGL(tim_extend_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st, counts);
+  TIM_LAUNCH_CHECK();
+  return TIM_OK;
+}
+
+extern "C" int tim_kv_write(tim_ctx *ctx, int32_t layer, const int32_t *row_off, int32_t n_rows, const void *k_rows,
+                            const void *v_rows, tim_stream stream) {
+  if (!ctx || !ctx->bound || !row_off || n_rows < 0 || layer < 0 || layer >= ctx->cfg.layers) return TIM_ERR_INVALID_ARG;
+  if (n_rows == 0) return TIM_OK;
+  if (!k_rows || !v_rows) return TIM_ERR_INVALID_ARG;
+  const int64_t total = 2 * (int64_t)n_rows * ctx->cfg.kv_heads * 16;
+  const int threads = 256;
+  hipLaunchKernelGGL(tim_write_rows_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0,
+                     tim_hs(stream), ctx->cfg, ctx->st, layer, row_off, n_rows, reinterpret_cast<const uint4 *>(k_rows),
+                     reinterpret_cast<const uint4 *>(v_rows));
   TIM_LAUNCH_CHECK();
   return TIM_OK;
 }

@@ -21,7 +21,7 @@ PLAN_HDR, PLAN_TOTALS = 16, 8
 TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_TILES = range(7)
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
-           "tim_seq_advance", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
+           "tim_seq_advance", "tim_seq_extend", "tim_kv_write", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
            "tim_decode_attn", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
@@ -59,6 +59,8 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_pool_reset": (C.c_int, [p, p]),
         "tim_tree_mark": (C.c_int, [p, p, i32, p]),
         "tim_seq_advance": (C.c_int, [p, p]),
+        "tim_seq_extend": (C.c_int, [p, p, p]),
+        "tim_kv_write": (C.c_int, [p, i32, p, i32, p, p, p]),
         "tim_kv_append": (C.c_int, [p, i32, p, p, p]),
         "tim_prune_plan": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
         "tim_kv_compact": (C.c_int, [p, C.POINTER(tim_plan), i32, i32, p]),
@@ -193,6 +195,19 @@ class Context:
 
     def tim_seq_advance(self):
         _check(lib().tim_seq_advance(self.handle, _stream()), "tim_seq_advance")
+
+    def tim_seq_extend(self, counts: torch.Tensor):
+        assert counts.dtype == torch.int32 and counts.is_cuda and counts.is_contiguous()
+        assert counts.shape[0] == self.cfg.max_batch
+        _check(lib().tim_seq_extend(self.handle, _ptr(counts), _stream()), "tim_seq_extend")
+
+    def tim_kv_write(self, layer: int, row_off: torch.Tensor, k_rows: torch.Tensor, v_rows: torch.Tensor):
+        assert row_off.dtype == torch.int32 and row_off.is_cuda and row_off.shape[0] == self.cfg.max_batch + 1
+        assert k_rows.dtype == torch.bfloat16 and v_rows.dtype == torch.bfloat16 and k_rows.is_cuda and v_rows.is_cuda
+        assert k_rows.is_contiguous() and v_rows.is_contiguous() and k_rows.shape == v_rows.shape
+        assert tuple(k_rows.shape[1:]) == (self.cfg.kv_heads, self.cfg.head_dim)
+        _check(lib().tim_kv_write(self.handle, layer, _ptr(row_off), k_rows.shape[0], _ptr(k_rows), _ptr(v_rows),
+                                  _stream()), "tim_kv_write")
 
     def tim_kv_append(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor):
         assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16

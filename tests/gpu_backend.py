@@ -68,6 +68,13 @@ class GpuRuntime:
     def advance(self):
         self.ctx.tim_seq_advance()
 
+    def extend_seq(self, counts):
+        self.ctx.tim_seq_extend(self._i32(counts))
+
+    def write_rows(self, layer, counts, k_rows_bits, v_rows_bits):
+        off = np.concatenate([[0], np.cumsum(np.asarray(counts, dtype=np.int64))]).astype(np.int32)
+        self.ctx.tim_kv_write(layer, self._i32(off), self._bf16(k_rows_bits), self._bf16(v_rows_bits))
+
     def append(self, layer, k_new_bits, v_new_bits):
         self.ctx.tim_kv_append(layer, self._bf16(k_new_bits), self._bf16(v_new_bits))
 

@@ -396,3 +396,56 @@ def test_in_forward_masked_variant(gb, threshold, cadence, spec_name):
         hidden = int((~ora.visible).sum())
     assert gpu.status() == 0 and hidden > 0
     assert list(ora.seq_len) == [p + steps for p in p0s]             # nothing was moved or shortened
+
+
+def test_tool_response_bulk_extend_then_prune(gb):
+    """A tool response enters as a batch of tokens (bulk extend + row write), its subtask
+    closes, and the flush evicts it together with the response (Sec. 2.1, Sec. 4.3)."""
+    from paper_2507_16784_amd.workload import tensors
+    from paper_2507_16784_amd.workload.tree import MARK_CLOSE, MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    tr = Trace(4000, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr, tr], [0, 0, 0], 1, {})
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=120, max_nodes=8,
+                              max_pages_per_seq=40)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    rng = np.random.default_rng(5)
+
+    def both(fn):
+        fn(ora); fn(gpu)
+
+    def bulk(counts, tag):
+        total = int(sum(counts))
+        both(lambda rt: rt.extend_seq(counts))
+        for layer in range(2):
+            k = tensors.bits(tensors.normal_bf16(tag, (layer, 0), (total, 2, 128), 1.0))
+            v = tensors.bits(tensors.normal_bf16(tag, (layer, 1), (total, 2, 128), 1.0))
+            both(lambda rt: rt.write_rows(layer, counts, k, v))
+        check_state(ora, gpu)
+
+    bulk([37, 5, 64], 1)                                              # prompts
+    both(lambda rt: rt.mark([(b, MARK_OPEN, 0, -1) for b in range(3)]))
+    bulk([10, 20, 3], 2)                                              # thoughts
+    both(lambda rt: rt.mark([(b, MARK_SUB_BEGIN, 0, -1) for b in range(3)] + [(b, MARK_OPEN, 1, -1) for b in range(3)]))
+    bulk([6, 6, 6], 3)                                                # the subtask asks for a tool
+    bulk([150, 0, 333], 4)                                            # tool responses of very different sizes
+    bulk([4, 9, 1], 5)                                                # the subtask's conclusion
+    both(lambda rt: rt.mark([(b, MARK_CLOSE, 1, -1) for b in range(3)] + [(b, MARK_SUB_END, 0, -1) for b in range(3)]))
+    bulk([7, 7, 7], 6)                                                # parent's conclusion so far
+    check_kv(ora, gpu)
+    ev = ora.prune_plan([0, 1, 2]); ora.kv_compact(ev, 0, 2); ora.commit(ev)
+    pl = gpu.prune_plan([0, 1, 2]); gpu.kv_compact(pl, 0, 2); gpu.commit(pl)
+    check_plan(ev, gpu.plan_view())
+    check_state(ora, gpu)
+    check_kv(ora, gpu)
+    assert list(ora.seq_len) == [37 + 10 + 7, 5 + 20 + 7, 64 + 3 + 7]  # response and subtask are gone
+    q = tensors.bits(tensors.normal_bf16(7, (0,), (3, 8, 128), 1.0))
+    for layer in range(2):
+        check_attention(gpu.decode_attn(layer, q, 128 ** -0.5), ora.decode_attn(layer, q, 128 ** -0.5))
+    # a batch that does not fit changes nothing
+    before = gpu.state()
+    both(lambda rt: rt.extend_seq([5000, 0, 0]))
+    assert gpu.status() == ora.status != 0
+    after = gpu.state()
+    for k in before:
+        assert np.array_equal(before[k], after[k]), k

@@ -173,3 +173,37 @@ def test_compacted_cache_attends_like_rope_at_the_new_positions():
     q9 = bf16.from_f64(rotate(q_raw, np.full(4, 9), 1.0e6))
     out = rt2.decode_attn(0, q9[None], 1.0)[0]
     assert np.allclose(out[0], bf16.to_f64(bf16.from_f64(v_raw[43, 0])), atol=1e-3)
+
+
+def test_bulk_extend_equals_repeated_advance_for_one_sequence_and_keeps_order_for_many():
+    a = OracleRuntime(_cfg(pages=16, batch=1, mp=16), 0)
+    b = OracleRuntime(_cfg(pages=16, batch=1, mp=16), 0)
+    for c in (5, 0, 27, 1, 16, 40):
+        assert a.extend_seq([c]) == 0
+        for _ in range(c):
+            assert b.advance() == 0
+        assert np.array_equal(a.page_table, b.page_table) and np.array_equal(a.seq_len, b.seq_len)
+        assert np.array_equal(a.free.free_ids(), b.free.free_ids())
+    # two sequences: all new pages of sequence 0 come before those of sequence 1 (hand-worked)
+    rt = OracleRuntime(_cfg(pages=8, batch=2, mp=4), 0)
+    assert rt.extend_seq([20, 33]) == 0                    # 2 pages, then 3 pages
+    assert list(rt.page_table[0, :2]) == [0, 1] and list(rt.page_table[1, :3]) == [2, 3, 4]
+    assert rt.extend_seq([12, 0]) == 0                     # 20 -> 32 tokens: still 2 pages
+    assert list(rt.seq_len) == [32, 33] and rt.free.top == 3
+    _check_conservation(rt)
+    # all or nothing
+    rt2 = OracleRuntime(_cfg(pages=3, batch=2, mp=4), 0)
+    assert rt2.extend_seq([17, 17]) == ERR_OOM_PAGES
+    assert list(rt2.seq_len) == [0, 0] and rt2.free.top == 3
+
+
+def test_write_rows_lands_on_the_last_positions():
+    rt = OracleRuntime(_cfg(pages=8, batch=2, mp=4), 0)
+    rt.extend_seq([3, 18])
+    rt.extend_seq([4, 2])
+    k = np.arange(6 * 128, dtype=np.uint16).reshape(6, 1, 128)
+    rt.write_rows(0, [4, 2], k, k + 1)
+    k0, v0 = rt.gather_kv(0, 0)
+    k1, v1 = rt.gather_kv(0, 1)
+    assert np.array_equal(k0[3:7], k[:4]) and np.array_equal(v0[3:7], k[:4] + 1)
+    assert np.array_equal(k1[18:20], k[4:]) and np.all(k0[:3] == 0) and np.all(k1[:18] == 0)
