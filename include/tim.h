@@ -24,8 +24,9 @@
  *   - Every call is asynchronous on the given stream (a hipStream_t passed as
  *     void*; NULL is the default stream), except tim_status(), which waits.
  *     One context serves one stream at a time.
- *   - Shapes: head_dim = 128, page_size = 16, q_heads = 4 * kv_heads.  Other
- *     values are rejected with TIM_ERR_INVALID_ARG.
+ *   - Shapes: head_dim = 128, q_heads = 4 * kv_heads, page_size = 16, or 1 (the paper's
+ *     own setting, Sec. 3.1; see "Page size 1" below).  Other values are rejected with
+ *     TIM_ERR_INVALID_ARG.
  *   - bf16 is the upper half of an IEEE binary32, round-to-nearest-even.
  *
  * Data layout
@@ -34,6 +35,13 @@
  *   stored rotated (RoPE, pairs (i, i + 64), theta_i = rope_base^(-2i/128)) at
  *   their current position.  A token with logical index t of sequence b lives
  *   in page page_table[b][t / 16], row t % 16.  "slot" = page * 16 + row.
+ *
+ * Page size 1
+ *   Every token owns a page (pool [layers][num_pages][kv_heads][1][128]), so a flush moves no
+ *   row: a survivor keeps its page, the page-table row is compacted as integers, the pruned
+ *   tokens' pages return to the free stack in ascending logical order, and tim_kv_compact
+ *   only re-rotates, in place, the keys behind the first pruned token.  tim_extend_attn and
+ *   the vector-ALU attention variant do not support it.
  *
  * Order of one decode step
  *   tim_tree_mark (structure seen at this boundary)
@@ -104,7 +112,7 @@ typedef struct {
   int32_t *lists_done;       /* device [max_batch], lists completed so far */
   float *attn_ws;            /* device scratch for split partials, see tim_attn_ws_bytes */
   int64_t attn_ws_bytes;
-  uint32_t *keep_mask;       /* device [max_batch][ceil(max_pages_per_seq / 2)], bit t%32 of word t/32 = token t is
+  uint32_t *keep_mask;       /* device [max_batch][ceil(max_pages_per_seq * page_size / 32)], bit t%32 of word t/32 = token t is
                                 visible; only the *_mask calls use it, may be NULL otherwise */
 } tim_state;
 

@@ -187,11 +187,18 @@ class OracleRuntime:
             sp.n = n
             sp.plan = Plan(kept_flags(n, ranges))
             m, f = sp.plan.n_kept, sp.plan.first_pruned
-            # pages wholly before the first pruned token stay where they are;
-            # if only a tail was pruned nothing moves and the boundary page stays too
-            sp.keep_pages = self._pages_of(f) if m == f else f // ps
-            sp.need = self._pages_of(m) - sp.keep_pages
-            sp.old_pages = self.page_table[b, sp.keep_pages : self._pages_of(n)].copy()
+            if ps == 1:
+                # the paper's page size (Sec. 3.1): every token owns a page, so a survivor simply
+                # keeps it; only the pruned tokens' pages go back, in ascending logical order
+                sp.keep_pages = f
+                sp.need = 0
+                sp.old_pages = self.page_table[b, np.flatnonzero(sp.plan.new_pos < 0)].copy()
+            else:
+                # pages wholly before the first pruned token stay where they are;
+                # if only a tail was pruned nothing moves and the boundary page stays too
+                sp.keep_pages = self._pages_of(f) if m == f else f // ps
+                sp.need = self._pages_of(m) - sp.keep_pages
+                sp.old_pages = self.page_table[b, sp.keep_pages : self._pages_of(n)].copy()
             ev.seqs.append(sp)
         total = sum(sp.need for sp in ev.seqs)
         if total > self.free.top:
@@ -205,6 +212,8 @@ class OracleRuntime:
             m = pl.n_kept
             sp.new_table = self.page_table[b].copy()
             sp.new_table[sp.keep_pages :] = -1
+            if ps == 1:
+                sp.new_table[:m] = self.page_table[b, pl.kept_idx]        # same pages, closed up
             for p in range(sp.keep_pages, sp.keep_pages + sp.need):
                 sp.new_table[p] = self.free.pop()
             moved = np.arange(sp.keep_pages * ps, m, dtype=np.int64)

@@ -254,7 +254,7 @@ __device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __bui
 
 #define AT_LAZY_MAX 8.0f
 
-template <bool OUT_BF16, bool MASKED>
+template <bool OUT_BF16, bool MASKED, bool PS1>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
                              void *__restrict__ out, float scale_log2, int cpb) {
@@ -295,34 +295,65 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   for (int chunk = slot; chunk < nchunks; chunk += used) {
     const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
     const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
-    // the wave's page ids of this chunk in one load: lane i holds page pg0 + i
-    const int my_pid = ptab[min(pg0 + (lane & (AT_PAGES_PER_WAVE - 1)), max(n_pages - 1, 0))];
+    // the wave's page ids of this chunk in one load: lane i holds page pg0 + i.  (With page
+    // size 1 a "page" below is a run of 16 tokens and every row has its own page id.)
+    int my_pid = 0;
+    if (!PS1) my_pid = ptab[min(pg0 + (lane & (AT_PAGES_PER_WAVE - 1)), max(n_pages - 1, 0))];
     for (int pg = pg0; pg < pg1; pg += 2) {
       const bool has_b = pg + 1 < pg1;
       // in-forward variant: visibility of the pair's 32 tokens (pairs start at even pages);
       // a pair without a visible token is not read at all
       uint32_t vis = 0xffffffffu;
       if (MASKED) {
-        vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * ((cfg.max_pages_per_seq + 1) / 2) + (pg >> 1)]);
+        vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * tim_mask_words(cfg) + (pg >> 1)]);
         if (vis == 0) continue;
       }
-      int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
-      int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
-      if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
-        tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
-        phys_a = phys_b = 0;
-      }
-      const int64_t tile_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-      const int64_t tile_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
       uint4 ka[4], kb[4], va[4], vb[4];
+      if (PS1) {
+        // one page per token: the K operand row j and the V rows 4g+i each bring their own id
+        const int ta = pg * TIM_PS, tb = has_b ? ta + TIM_PS : ta, last = n - 1;
+        int ids[10];
+        ids[0] = ptab[min(ta + j, last)];
+        ids[1] = ptab[min(tb + j, last)];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ka[s] = kpool[tile_a + j * 16 + 4 * s + g];
+        for (int i = 0; i < 4; ++i) {
+          ids[2 + i] = ptab[min(ta + 4 * g + i, last)];
+          ids[6 + i] = ptab[min(tb + 4 * g + i, last)];
+        }
 #pragma unroll
-      for (int s = 0; s < 4; ++s) kb[s] = kpool[tile_b + j * 16 + 4 * s + g];
+        for (int i = 0; i < 10; ++i) {
+          if (ids[i] < 0 || ids[i] >= cfg.num_pages) {  // never dereference a bad page id
+            tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+            ids[i] = 0;
+          }
+        }
+        const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) va[i] = vpool[tile_a + (4 * g + i) * 16 + j];
+        for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) vb[i] = vpool[tile_b + (4 * g + i) * 16 + j];
+        for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) va[i] = vpool[((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vb[i] = vpool[((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j];
+      } else {
+        int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
+        int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
+        if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
+          tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
+          phys_a = phys_b = 0;
+        }
+        const int64_t tile_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+        const int64_t tile_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ka[s] = kpool[tile_a + j * 16 + 4 * s + g];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) kb[s] = kpool[tile_b + j * 16 + 4 * s + g];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) va[i] = vpool[tile_a + (4 * g + i) * 16 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vb[i] = vpool[tile_b + (4 * g + i) * 16 + j];
+      }
 
       // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
       const int left_a = n - pg * TIM_PS;
@@ -487,8 +518,9 @@ extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
 template <int IMPL, bool OUT_BF16>  // 0 = vector ALU, 1 = matrix cores, 2 = matrix cores with visibility mask
 static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
                       float scale_log2, int cpb) {
-  auto kernel = IMPL == 2   ? tim_attn_partial_mfma_kernel<OUT_BF16, true>
-                : IMPL == 1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false>
+  const bool ps1 = ctx->cfg.page_size == 1;
+  auto kernel = IMPL == 2   ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, true, true> : tim_attn_partial_mfma_kernel<OUT_BF16, true, false>)
+                : IMPL == 1 ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false, true> : tim_attn_partial_mfma_kernel<OUT_BF16, false, false>)
                             : tim_attn_partial_kernel<OUT_BF16>;
   const uint4 *q4 = reinterpret_cast<const uint4 *>(q);
   if (ctx->timing_on && ctx->timing_n < (int)ctx->ev_start.size()) {
@@ -537,10 +569,11 @@ extern "C" int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out) {
 static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                      int32_t max_seq_len, tim_stream stream, bool masked) {
   if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers ||
-      (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask))
+      (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask) ||
+      (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
     return TIM_ERR_INVALID_ARG;
   const tim_config &cfg = ctx->cfg;
-  const int full = cfg.max_pages_per_seq * TIM_PS;
+  const int full = cfg.max_pages_per_seq * cfg.page_size;
   const int bound = (max_seq_len == 0 || max_seq_len > full) ? full : max_seq_len;
   const int max_pages = (bound + TIM_PS - 1) / TIM_PS;
   const int nchunks = (max_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;

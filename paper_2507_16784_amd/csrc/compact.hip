@@ -144,6 +144,96 @@ tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int la
   }
 }
 
+// Page size 1 (the paper's setting): survivors keep their pages, so a flush moves no row at
+// all; only the keys behind the first pruned token are re-rotated where they lie (2 x 2 KiB
+// per token per layer instead of 2 x 4 KiB, values untouched).  Work items are (tile of 32
+// such tokens, layer group); thread (t, c) owns token t's eight rotation pairs as above and
+// reads and writes the same addresses, so there is no hazard between threads.
+__global__ void __launch_bounds__(CP_THREADS)
+tim_rotate_inplace_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer_begin, int layer_end,
+                          double theta1, double theta8) {
+  if (!pl.totals[TIM_TOT_OK]) return;
+  const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
+  const int64_t n_work = (int64_t)pl.totals[TIM_TOT_EXT_TILES] * groups;
+  const int tid = threadIdx.x, t = tid >> 3, c = tid & 7;
+  const int T = cfg.max_pages_per_seq * cfg.page_size;
+  const int hkv = cfg.kv_heads;
+  uint4 *kw = reinterpret_cast<uint4 *>(st.k_pool);
+  for (int64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
+    const int tile = (int)(w / groups), grp = (int)(w % groups);
+    int lo = 0, hi = n_seqs - 1;  // last e with EXT_TILE_OFF[e] <= tile
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (pl.hdr[(int64_t)mid * TIM_PLAN_HDR + TIM_HDR_EXT_TILE_OFF] <= tile) lo = mid; else hi = mid - 1;
+    }
+    const int e = lo;
+    const int32_t *hdr = pl.hdr + (int64_t)e * TIM_PLAN_HDR;
+    if (hdr[TIM_HDR_BAD]) continue;
+    const int m = hdr[TIM_HDR_N_KEPT], f = hdr[TIM_HDR_FIRST_PRUNED];
+    const int l0 = layer_begin + grp * CP_LAYERS_PER_BLOCK, l1 = min(l0 + CP_LAYERS_PER_BLOCK, layer_end);
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      const int j = f + (tile - hdr[TIM_HDR_EXT_TILE_OFF]) * 32 + half * 16 + t;
+      if (j >= m) continue;
+      const int d = pl.delta[(int64_t)e * T + j];
+      const int slot = pl.src_slot[(int64_t)e * T + j];
+      if (d == 0) continue;
+      if (slot < 0 || slot >= cfg.num_pages) {
+        tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+        continue;
+      }
+      float cs[8], sn[8];
+      double th = 1.0;
+      for (int q = 0; q < c; ++q) th *= theta8;
+      const double two_pi_hi = 6.283185307179586232e+00, two_pi_lo = 2.449293598294706414e-16;
+      const double inv_two_pi = 1.591549430918953456e-01;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const double a = (double)d * th;
+        const double n2 = rint(a * inv_two_pi);
+        double r = fma(-n2, two_pi_hi, a);
+        r = fma(-n2, two_pi_lo, r);
+        sincosf((float)r, &sn[k], &cs[k]);
+        th *= theta1;
+      }
+      for (int layer = l0; layer < l1; ++layer) {
+        const int64_t base = (((int64_t)layer * cfg.num_pages + slot) * hkv) * 16 + c;  // uint4 units, row = 16
+        for (int h = 0; h < hkv; h += 2) {
+          const bool two = h + 1 < hkv;
+          uint4 klo[2], khi[2];
+          klo[0] = kw[base + (int64_t)h * 16];
+          khi[0] = kw[base + (int64_t)h * 16 + 8];
+          if (two) {
+            klo[1] = kw[base + (int64_t)(h + 1) * 16];
+            khi[1] = kw[base + (int64_t)(h + 1) * 16 + 8];
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            uint32_t *a = reinterpret_cast<uint32_t *>(&klo[u]);
+            uint32_t *b = reinterpret_cast<uint32_t *>(&khi[u]);
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+              const float x0 = bf_lo(a[wd]), x1 = bf_hi(a[wd]);
+              const float y0 = bf_lo(b[wd]), y1 = bf_hi(b[wd]);
+              const float c0 = cs[2 * wd], s0 = sn[2 * wd], c1 = cs[2 * wd + 1], s1 = sn[2 * wd + 1];
+              const float rx0 = fmaf(x0, c0, -(y0 * s0)), ry0 = fmaf(y0, c0, x0 * s0);
+              const float rx1 = fmaf(x1, c1, -(y1 * s1)), ry1 = fmaf(y1, c1, x1 * s1);
+              a[wd] = bf_pack(rx0, rx1);
+              b[wd] = bf_pack(ry0, ry1);
+            }
+          }
+          kw[base + (int64_t)h * 16] = klo[0];
+          kw[base + (int64_t)h * 16 + 8] = khi[0];
+          if (two) {
+            kw[base + (int64_t)(h + 1) * 16] = klo[1];
+            kw[base + (int64_t)(h + 1) * 16 + 8] = khi[1];
+          }
+        }
+      }
+    }
+  }
+}
+
 extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_begin, int32_t layer_end,
                               tim_stream stream) {
   if (!ctx || !ctx->bound || !plan || !plan->hdr || !plan->totals || !plan->src_slot || !plan->dst_slot ||
@@ -153,6 +243,12 @@ extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_
   if (layer_begin == layer_end) return TIM_OK;
   // enough two-wave blocks to keep every CU's load queues full; they stride over the items
   dim3 grid(16 * ctx->n_cu);
+  if (ctx->cfg.page_size == 1) {
+    hipLaunchKernelGGL(tim_rotate_inplace_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
+                       plan->n_seqs, layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
+    TIM_LAUNCH_CHECK();
+    return TIM_OK;
+  }
   hipLaunchKernelGGL(tim_compact_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
                      plan->n_seqs, layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
   TIM_LAUNCH_CHECK();

@@ -9,12 +9,12 @@
 extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   if (!out || !cfg) return TIM_ERR_INVALID_ARG;
   *out = nullptr;
-  if (cfg->head_dim != TIM_D || cfg->page_size != TIM_PS || cfg->kv_heads <= 0 ||
+  if (cfg->head_dim != TIM_D || (cfg->page_size != TIM_PS && cfg->page_size != 1) || cfg->kv_heads <= 0 ||
       cfg->q_heads != TIM_G * cfg->kv_heads || cfg->layers <= 0 || cfg->num_pages <= 0 || cfg->max_batch <= 0 ||
       cfg->max_pages_per_seq <= 0 || cfg->max_nodes <= 0 || !(cfg->rope_base > 1.0f))
     return TIM_ERR_INVALID_ARG;
   // slots are int32: page * 16 + row must not overflow
-  if ((int64_t)cfg->num_pages * TIM_PS > INT32_MAX || (int64_t)cfg->max_pages_per_seq * TIM_PS > INT32_MAX / 2)
+  if ((int64_t)cfg->num_pages * cfg->page_size > INT32_MAX || (int64_t)cfg->max_pages_per_seq * cfg->page_size > INT32_MAX / 2)
     return TIM_ERR_INVALID_ARG;
   tim_ctx *c = new (std::nothrow) tim_ctx();
   if (!c) return TIM_ERR_INVALID_ARG;

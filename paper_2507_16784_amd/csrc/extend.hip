@@ -223,6 +223,7 @@ extern "C" int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan
                                int32_t n_ext_total, float sm_scale, int32_t out_dtype, tim_stream stream) {
   if (!ctx || !ctx->bound || !plan || !plan->hdr || !plan->totals || plan->n_seqs <= 0 ||
       plan->n_seqs > plan->max_seqs || layer < 0 || layer >= ctx->cfg.layers || n_ext_total < 0 ||
+      ctx->cfg.page_size != TIM_PS ||  // the extend kernel reads 16-token pages only
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16))
     return TIM_ERR_INVALID_ARG;
   if (n_ext_total == 0) return TIM_OK;

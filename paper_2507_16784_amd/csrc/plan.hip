@@ -19,7 +19,7 @@ tim_plan_scan_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *_
   const int e = blockIdx.x, tid = threadIdx.x;
   const int b = seq_ids[e];
   int32_t *hdr = pl.hdr + (int64_t)e * TIM_PLAN_HDR;
-  const int T = cfg.max_pages_per_seq * TIM_PS;
+  const int T = cfg.max_pages_per_seq * cfg.page_size;
   if (tid == 0) {
     s_first = 0x7fffffff;
     s_bad = 0;
@@ -133,10 +133,18 @@ tim_plan_scan_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *_
     hdr[TIM_HDR_FIRST_PRUNED] = f;
     // whole pages before the first pruned token stay in place; when only a tail was
     // pruned (m == f, which includes "nothing pruned") the boundary page stays as well
-    const int keep = (m == f) ? (f + TIM_PS - 1) / TIM_PS : f / TIM_PS;
-    hdr[TIM_HDR_KEEP_PAGES] = keep;
-    hdr[TIM_HDR_NEED] = (m + TIM_PS - 1) / TIM_PS - keep;
-    hdr[TIM_HDR_PUSH] = (n + TIM_PS - 1) / TIM_PS - keep;
+    if (cfg.page_size == 1) {
+      // page size 1 (the paper's setting): a survivor keeps its page, nothing is copied; the
+      // pruned tokens' pages are returned and the table is compacted as integers
+      hdr[TIM_HDR_KEEP_PAGES] = f;
+      hdr[TIM_HDR_NEED] = 0;
+      hdr[TIM_HDR_PUSH] = n - m;
+    } else {
+      const int keep = (m == f) ? (f + cfg.page_size - 1) / cfg.page_size : f / cfg.page_size;
+      hdr[TIM_HDR_KEEP_PAGES] = keep;
+      hdr[TIM_HDR_NEED] = (m + cfg.page_size - 1) / cfg.page_size - keep;
+      hdr[TIM_HDR_PUSH] = (n + cfg.page_size - 1) / cfg.page_size - keep;
+    }
     hdr[TIM_HDR_EXT] = m - f;  // survivors behind the first pruned token (0 when nothing moves)
   }
 }
@@ -196,8 +204,16 @@ __global__ void tim_plan_slots_kernel(tim_config cfg, tim_state st, tim_plan pl)
   const int b = hdr[TIM_HDR_SEQ], m = hdr[TIM_HDR_N_KEPT];
   const int keep = hdr[TIM_HDR_KEEP_PAGES], need = hdr[TIM_HDR_NEED], off = hdr[TIM_HDR_PAGE_OFF];
   const int top = pl.totals[TIM_TOT_TOP_BEFORE];
-  const int T = cfg.max_pages_per_seq * TIM_PS;
+  const int T = cfg.max_pages_per_seq * cfg.page_size;
   const int32_t *old_row = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
+  if (cfg.page_size == 1) {  // survivors keep their pages: the new row is the old one gathered by kept_idx
+    if (j < cfg.max_pages_per_seq) {
+      const int v = j < m ? old_row[pl.kept_idx[(int64_t)e * T + j]] : -1;
+      pl.new_table[(int64_t)e * cfg.max_pages_per_seq + j] = v;
+      if (j >= keep && j < m) pl.src_slot[(int64_t)e * T + j] = pl.dst_slot[(int64_t)e * T + j] = v;
+    }
+    return;
+  }
   if (j < cfg.max_pages_per_seq) {
     int v = -1;
     if (j < keep)
@@ -206,11 +222,11 @@ __global__ void tim_plan_slots_kernel(tim_config cfg, tim_state st, tim_plan pl)
       v = st.free_stack[top - 1 - (off + (j - keep))];
     pl.new_table[(int64_t)e * cfg.max_pages_per_seq + j] = v;
   }
-  if (j >= keep * TIM_PS && j < m) {
+  if (j >= keep * cfg.page_size && j < m) {
     const int src = pl.kept_idx[(int64_t)e * T + j];
-    pl.src_slot[(int64_t)e * T + j] = old_row[src / TIM_PS] * TIM_PS + src % TIM_PS;
-    const int fresh = st.free_stack[top - 1 - (off + (j / TIM_PS - keep))];
-    pl.dst_slot[(int64_t)e * T + j] = fresh * TIM_PS + j % TIM_PS;
+    pl.src_slot[(int64_t)e * T + j] = old_row[src / cfg.page_size] * cfg.page_size + src % cfg.page_size;
+    const int fresh = st.free_stack[top - 1 - (off + (j / cfg.page_size - keep))];
+    pl.dst_slot[(int64_t)e * T + j] = fresh * cfg.page_size + j % cfg.page_size;
   }
 }
 
@@ -222,8 +238,16 @@ __global__ void tim_plan_commit_kernel(tim_config cfg, tim_state st, tim_plan pl
   if (hdr[TIM_HDR_BAD]) return;
   const int b = hdr[TIM_HDR_SEQ], n = hdr[TIM_HDR_N], m = hdr[TIM_HDR_N_KEPT];
   const int keep = hdr[TIM_HDR_KEEP_PAGES], push = hdr[TIM_HDR_PUSH], push_off = hdr[TIM_HDR_PUSH_OFF];
-  const int T = cfg.max_pages_per_seq * TIM_PS;
-  if (i < cfg.max_pages_per_seq) {
+  const int T = cfg.max_pages_per_seq * cfg.page_size;
+  if (cfg.page_size == 1) {
+    if (i < cfg.max_pages_per_seq && i >= keep) {
+      int32_t *slot = st.page_table + (int64_t)b * cfg.max_pages_per_seq + i;
+      // a pruned token returns its page; its rank among the pruned tokens keeps the order ascending
+      if (i < n && pl.new_pos[(int64_t)e * T + i] < 0)
+        st.free_stack[pl.totals[TIM_TOT_TOP_AFTER_POP] + push_off + (i - pl.rank[(int64_t)e * (T + 1) + i])] = *slot;
+      *slot = pl.new_table[(int64_t)e * cfg.max_pages_per_seq + i];
+    }
+  } else if (i < cfg.max_pages_per_seq) {
     int32_t *slot = st.page_table + (int64_t)b * cfg.max_pages_per_seq + i;
     if (i >= keep) {
       if (i < keep + push) st.free_stack[pl.totals[TIM_TOT_TOP_AFTER_POP] + push_off + (i - keep)] = *slot;
@@ -261,7 +285,7 @@ tim_prune_mask_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *
     if (tid == 0) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
     return;
   }
-  const int T = cfg.max_pages_per_seq * TIM_PS;
+  const int T = cfg.max_pages_per_seq * cfg.page_size;
   const int n = st.seq_len[b];
   int32_t *cover = pl.cover + (int64_t)e * (T + 1);
   int32_t *vis = pl.new_pos + (int64_t)e * T;
@@ -311,7 +335,7 @@ tim_prune_mask_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *
   __threadfence_block();
   __syncthreads();
   const int words = (n + 31) / 32;
-  uint32_t *mask = st.keep_mask + (int64_t)b * ((cfg.max_pages_per_seq + 1) / 2);
+  uint32_t *mask = st.keep_mask + (int64_t)b * tim_mask_words(cfg);
   for (int w = tid; w < words; w += PLAN_THREADS) {
     uint32_t bits = 0;
     for (int k = 0; k < 32; ++k) {
@@ -340,7 +364,7 @@ extern "C" int tim_prune_plan(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_se
   hipLaunchKernelGGL(tim_plan_pages_kernel, dim3(1), dim3(n_seqs <= 64 ? 64 : 1024), 0, s, ctx->cfg, ctx->st, *plan,
                      n_seqs);
   TIM_LAUNCH_CHECK();
-  const int T = ctx->cfg.max_pages_per_seq * TIM_PS;
+  const int T = ctx->cfg.max_pages_per_seq * ctx->cfg.page_size;
   hipLaunchKernelGGL(tim_plan_slots_kernel, dim3((T + 255) / 256, n_seqs), dim3(256), 0, s, ctx->cfg, ctx->st, *plan);
   TIM_LAUNCH_CHECK();
   return TIM_OK;

@@ -18,7 +18,7 @@ __global__ void tim_reset_kernel(tim_config cfg, tim_state st) {
     st.node_list_order[k] = -1;
   }
   if (st.keep_mask) {
-    const int64_t nw = (int64_t)cfg.max_batch * ((cfg.max_pages_per_seq + 1) / 2);
+    const int64_t nw = (int64_t)cfg.max_batch * tim_mask_words(cfg);
     for (int64_t k = i; k < nw; k += stride) st.keep_mask[k] = 0xffffffffu;
   }
   for (int64_t k = i; k < cfg.max_batch; k += stride) {
@@ -88,9 +88,9 @@ __global__ void __launch_bounds__(1024) tim_advance_kernel(tim_config cfg, tim_s
   int cnt = 0;
   for (int b = tid; b < cfg.max_batch; b += blockDim.x) {
     const int n = st.seq_len[b];
-    if (n % TIM_PS == 0) {
+    if (n % cfg.page_size == 0) {
       ++cnt;
-      if (n / TIM_PS >= cfg.max_pages_per_seq) atomicOr(&s_bad, 1);
+      if (n / cfg.page_size >= cfg.max_pages_per_seq) atomicOr(&s_bad, 1);
     }
   }
   int total;
@@ -111,12 +111,12 @@ __global__ void __launch_bounds__(1024) tim_advance_kernel(tim_config cfg, tim_s
     int need = 0, n = 0;
     if (b < cfg.max_batch) {
       n = st.seq_len[b];
-      need = (n % TIM_PS == 0) ? 1 : 0;
+      need = (n % cfg.page_size == 0) ? 1 : 0;
     }
     int chunk_total;
     const int incl = tim_block_incl_scan(need, smem, &chunk_total);
     if (b < cfg.max_batch) {
-      if (need) st.page_table[(int64_t)b * cfg.max_pages_per_seq + n / TIM_PS] = st.free_stack[top - 1 - (base + incl - 1)];
+      if (need) st.page_table[(int64_t)b * cfg.max_pages_per_seq + n / cfg.page_size] = st.free_stack[top - 1 - (base + incl - 1)];
       st.seq_len[b] = n + 1;
     }
     base += chunk_total;
@@ -141,7 +141,7 @@ __global__ void __launch_bounds__(1024) tim_extend_kernel(tim_config cfg, tim_st
       atomicOr(&s_bad, 2);
       continue;
     }
-    const int have = (n + TIM_PS - 1) / TIM_PS, want = (n + c + TIM_PS - 1) / TIM_PS;
+    const int have = (n + cfg.page_size - 1) / cfg.page_size, want = (n + c + cfg.page_size - 1) / cfg.page_size;
     if (want > cfg.max_pages_per_seq) atomicOr(&s_bad, 1);
     cnt += want - have;
   }
@@ -163,8 +163,8 @@ __global__ void __launch_bounds__(1024) tim_extend_kernel(tim_config cfg, tim_st
     if (b < cfg.max_batch) {
       n = st.seq_len[b];
       c = counts[b];
-      have = (n + TIM_PS - 1) / TIM_PS;
-      need = (n + c + TIM_PS - 1) / TIM_PS - have;
+      have = (n + cfg.page_size - 1) / cfg.page_size;
+      need = (n + c + cfg.page_size - 1) / cfg.page_size - have;
     }
     int chunk_total;
     const int incl = tim_block_incl_scan(need, smem, &chunk_total);
@@ -200,7 +200,7 @@ __global__ void tim_write_rows_kernel(tim_config cfg, tim_state st, int layer, c
   const int b = lo, c = row_off[b + 1] - row_off[b];
   const int t = st.seq_len[b] - c + (row - row_off[b]);
   if (row >= row_off[cfg.max_batch] || t < 0) return;
-  const int page = st.page_table[(int64_t)b * cfg.max_pages_per_seq + t / TIM_PS];
+  const int page = st.page_table[(int64_t)b * cfg.max_pages_per_seq + t / cfg.page_size];
   if (page < 0 || page >= cfg.num_pages) {
     tim_set_status(st.status, TIM_ERR_INVALID_ARG);
     return;
@@ -208,7 +208,7 @@ __global__ void tim_write_rows_kernel(tim_config cfg, tim_state st, int layer, c
   const int64_t tile = ((int64_t)layer * cfg.num_pages + page) * cfg.kv_heads + h;
   uint4 *pool = reinterpret_cast<uint4 *>(which ? st.v_pool : st.k_pool);
   const uint4 *src = which ? v_rows : k_rows;
-  pool[tile * (TIM_TILE_BYTES / 16) + (t % TIM_PS) * 16 + piece] = src[((int64_t)row * cfg.kv_heads + h) * 16 + piece];
+  pool[tile * (cfg.page_size * 16) + (t % cfg.page_size) * 16 + piece] = src[((int64_t)row * cfg.kv_heads + h) * 16 + piece];
 }
 
 // ---- append the pending token's K/V row of one layer ------------------------------------
@@ -227,7 +227,7 @@ __global__ void tim_append_kernel(tim_config cfg, tim_state st, int layer, const
   const int n = st.seq_len[b];
   if (n <= 0) return;
   const int t = n - 1;
-  const int page = st.page_table[(int64_t)b * cfg.max_pages_per_seq + t / TIM_PS];
+  const int page = st.page_table[(int64_t)b * cfg.max_pages_per_seq + t / cfg.page_size];
   if (page < 0 || page >= cfg.num_pages) {
     tim_set_status(st.status, TIM_ERR_INVALID_ARG);
     return;
@@ -235,14 +235,14 @@ __global__ void tim_append_kernel(tim_config cfg, tim_state st, int layer, const
   const int64_t tile = ((int64_t)layer * cfg.num_pages + page) * cfg.kv_heads + h;
   uint4 *pool = reinterpret_cast<uint4 *>(which ? st.v_pool : st.k_pool);
   const uint4 *src = which ? v_new : k_new;
-  pool[tile * (TIM_TILE_BYTES / 16) + (t % TIM_PS) * 16 + piece] = src[(int64_t)bh * 16 + piece];
+  pool[tile * (cfg.page_size * 16) + (t % cfg.page_size) * 16 + piece] = src[(int64_t)bh * 16 + piece];
 }
 
 // ---- accounting ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024) tim_stats_kernel(tim_config cfg, tim_state st, int32_t *out) {
   __shared__ int smem[17];
   int cnt = 0;
-  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) cnt += (st.seq_len[b] + TIM_PS - 1) / TIM_PS;
+  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) cnt += (st.seq_len[b] + cfg.page_size - 1) / cfg.page_size;
   int total;
   tim_block_incl_scan(cnt, smem, &total);
   if (threadIdx.x == 0) {

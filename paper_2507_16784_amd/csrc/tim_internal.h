@@ -9,7 +9,7 @@
 #include "tim.h"
 
 #define TIM_D 128          // head dim
-#define TIM_PS 16          // tokens per page
+#define TIM_PS 16          // tokens per page in the default layout; page size 1 (the paper's) is the other one
 #define TIM_G 4            // query heads per KV head
 #define TIM_ROW_BYTES 256  // one bf16 row of TIM_D
 #define TIM_TILE_BYTES (TIM_PS * TIM_ROW_BYTES)  // one (page, kv head) tile: 4 KiB
@@ -40,6 +40,11 @@ struct RopeFreq {
 #define TIM_LAUNCH_CHECK() TIM_HIP_CHECK(hipGetLastError())
 
 static inline hipStream_t tim_hs(tim_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+// words per sequence of the visibility mask: one bit per logical token
+__host__ __device__ __forceinline__ int tim_mask_words(const tim_config &cfg) {
+  return (cfg.max_pages_per_seq * cfg.page_size + 31) / 32;
+}
 
 __device__ __forceinline__ void tim_set_status(int32_t *status, int32_t err) { atomicCAS(status, 0, err); }
 

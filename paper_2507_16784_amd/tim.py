@@ -161,7 +161,7 @@ class Context:
         self.node_list_order = torch.full((max_batch, max_nodes), -1, **i32)
         self.n_nodes = torch.zeros(max_batch, **i32)
         self.lists_done = torch.zeros(max_batch, **i32)
-        self.keep_mask = torch.full((max_batch, (max_pages_per_seq + 1) // 2), -1, **i32)   # all bits set
+        self.keep_mask = torch.full((max_batch, (max_pages_per_seq * page_size + 31) // 32), -1, **i32)  # all bits set
         ws_bytes = lib().tim_attn_ws_bytes(C.byref(self.cfg))
         self.attn_ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=device)
         self.state = tim_state(

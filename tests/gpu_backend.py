@@ -55,8 +55,9 @@ class GpuRuntime:
         c = self.ctx
         n = k_bits.shape[0]
         t = torch.arange(n, device=self.dev)
-        pages = c.page_table[b, (t // 16)].long()
-        rows = t % 16
+        ps = self.cfg.page_size
+        pages = c.page_table[b, (t // ps)].long()
+        rows = t % ps
         c.k_pool[layer, pages, :, rows] = self._bf16(k_bits)
         c.v_pool[layer, pages, :, rows] = self._bf16(v_bits)
 
@@ -133,8 +134,9 @@ class GpuRuntime:
         c = self.ctx
         n = int(c.seq_len[b].item())
         t = torch.arange(n, device=self.dev)
-        pages = c.page_table[b, (t // 16)].long()
-        rows = t % 16
+        ps = self.cfg.page_size
+        pages = c.page_table[b, (t // ps)].long()
+        rows = t % ps
         return tensors.bits(c.k_pool[layer, pages, :, rows].cpu()), tensors.bits(c.v_pool[layer, pages, :, rows].cpu())
 
     def status(self):

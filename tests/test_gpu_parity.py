@@ -449,3 +449,26 @@ def test_tool_response_bulk_extend_then_prune(gb):
     after = gpu.state()
     for k in before:
         assert np.array_equal(before[k], after[k]), k
+
+
+@pytest.mark.parametrize("threshold,cadence", [(0, 1), (2, 5)])
+def test_page_size_one_small_events(gb, threshold, cadence):
+    """Page size 1: survivors keep their pages, keys are re-rotated in place; frequent flushes."""
+    seeds, p0s, steps = [71, 72, 73], [37, 64, 150], 100
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(cadence, steps, 3))
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=400, page_size=1)
+    replay(gb, wl, cfg, threshold, 6, 1.0, 128 ** -0.5)
+
+
+def test_page_size_one_config1_and_config2_shapes(gb):
+    """Page size 1 at configuration-1 size (one flush) and configuration-2 shape (32/8 heads, flush every 8)."""
+    p0, steps = 4096, 3
+    wl = Workload([generate(1, p0 + steps + 1, SPEC_C1)], [p0], steps, {0: [0]})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=64, page_size=1)
+    ora, _ = replay(gb, wl, cfg, 1, 1, 128 ** -0.5, 128 ** -0.5)
+    assert ora.seq_len[0] < p0
+    p0, steps = 8192 - 32, 32
+    wl = Workload([generate(3, p0 + steps + 1, SPEC_C2)], [p0], steps, every(8, steps, 1))
+    cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=64, page_size=1)
+    replay(gb, wl, cfg, 1, 3, 1.0, 128 ** -0.5, attend_every=4)

@@ -207,3 +207,39 @@ def test_write_rows_lands_on_the_last_positions():
     k1, v1 = rt.gather_kv(0, 1)
     assert np.array_equal(k0[3:7], k[:4]) and np.array_equal(v0[3:7], k[:4] + 1)
     assert np.array_equal(k1[18:20], k[4:]) and np.all(k0[:3] == 0) and np.all(k1[:18] == 0)
+
+
+def test_page_size_one_keeps_survivor_pages_and_returns_the_rest_in_order():
+    """The paper's own page size (Sec. 3.1): nothing is copied.  Hand-worked: 12 tokens on pages
+    0..11, list = tokens 3..7 -> survivors keep pages [0,1,2,8,9,10,11], pages 3..7 are pushed in
+    that order, keys behind the gap are re-rotated in place by -5."""
+    cfg = Config(layers=1, q_heads=4, kv_heads=1, head_dim=128, page_size=1, num_pages=16, max_batch=1,
+                 max_pages_per_seq=16, max_nodes=4)
+    rt = OracleRuntime(cfg, 0)
+    rng = np.random.default_rng(1)
+    raw = rng.standard_normal((12, 1, 128))
+    rt.mark([(0, MARK_OPEN, 0, -1)])
+    for t in range(12):
+        if t == 3:
+            rt.mark([(0, MARK_SUB_BEGIN, 0, -1)])
+        if t == 8:
+            rt.mark([(0, MARK_SUB_END, 0, -1)])
+        rt.advance()
+        rt.append(0, bf16.from_f64(rotate(raw[t], np.array([t]), 1.0e6))[None], bf16.from_f64(raw[t])[None])
+    assert list(rt.page_table[0, :12]) == list(range(12)) and list(rt.free.free_ids()) == [15, 14, 13, 12]
+    k_before, v_before = rt.gather_kv(0, 0)
+    ev = rt.prune_plan([0])
+    sp = ev.seqs[0]
+    assert (sp.keep_pages, sp.need, list(sp.old_pages)) == (3, 0, [3, 4, 5, 6, 7])
+    assert list(sp.src_slot) == list(sp.dst_slot) == [8, 9, 10, 11] and list(sp.moved_delta) == [-5] * 4
+    rt.kv_compact(ev, 0, 1); rt.commit(ev)
+    assert list(rt.page_table[0, :8]) == [0, 1, 2, 8, 9, 10, 11, -1] and rt.seq_len[0] == 7
+    assert list(rt.free.free_ids()) == [15, 14, 13, 12, 3, 4, 5, 6, 7]
+    k_after, v_after = rt.gather_kv(0, 0)
+    assert np.array_equal(v_after, v_before[[0, 1, 2, 8, 9, 10, 11]])
+    assert np.array_equal(k_after[:3], k_before[:3])
+    want = bf16.from_f64(rotate(bf16.to_f64(k_before[8:12]), np.full((4, 1), -5), 1.0e6))
+    assert np.array_equal(k_after[3:], want)
+    exact = rotate(raw[8:12], np.arange(3, 7)[:, None], 1.0e6)          # keys placed directly at 3..6
+    assert np.max(np.abs(bf16.to_f64(k_after[3:]) - exact)) < 2.0 ** -6 * np.max(np.abs(exact))
+    _check_conservation(rt)
