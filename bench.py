@@ -44,24 +44,25 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed):
+def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, page_size=16):
     import numpy as np
     from paper_2507_16784_amd.workload.state import scattered_pages
 
     B = len(wl.traces)
     longest = max(p + wl.steps for p in wl.preload)
-    mp = (longest + 15) // 16 + 1
-    used = sum((p + 15) // 16 for p in wl.preload)
-    num_pages = used + headroom_pages
+    ps = page_size
+    mp = (longest + ps - 1) // ps + 1
+    used = sum((p + ps - 1) // ps for p in wl.preload)
+    num_pages = used + headroom_pages * (16 // ps)
     max_nodes = max(t.n_nodes for t in wl.traces)
-    per_layer = 2 * num_pages * shape.kv_heads * 16 * 128 * 2
+    per_layer = 2 * num_pages * shape.kv_heads * ps * 128 * 2
     free_b, total_b = torch.cuda.mem_get_info()
     budget = free_b - (6 << 30)          # leave room for plans, workspaces, logs
     fit = max(1, min(shape.layers, int(budget // per_layer)))
     L = min(layers_alloc or shape.layers, fit)
     log(f"[bench] pool: {num_pages} pages x {L} layers = {per_layer * L / 1e9:.1f} GB "
         f"(HBM free {free_b / 1e9:.1f} GB of {total_b / 1e9:.1f} GB)")
-    shp = (L, num_pages, shape.kv_heads, 16, 128)
+    shp = (L, num_pages, shape.kv_heads, ps, 128)
     k_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
     v_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
     g = torch.Generator(device="cuda")
@@ -69,8 +70,9 @@ def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed):
     for l in range(L):
         k_pool[l].normal_(0.0, shape.kv_scale, generator=g)
         v_pool[l].normal_(0.0, shape.kv_scale, generator=g)
-    ctx = tim.Context(L, shape.q_heads, shape.kv_heads, num_pages, B, mp, max_nodes, pools=(k_pool, v_pool))
-    tables, free_ids = scattered_pages(seed, num_pages, 16, wl.preload)
+    ctx = tim.Context(L, shape.q_heads, shape.kv_heads, num_pages, B, mp, max_nodes, page_size=ps,
+                      pools=(k_pool, v_pool))
+    tables, free_ids = scattered_pages(seed, num_pages, ps, wl.preload)
     pt = np.full((B, mp), -1, dtype=np.int32)
     for b, t in enumerate(tables):
         pt[b, : len(t)] = t
@@ -199,10 +201,28 @@ def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
     assert status == 0, f"device status {status}"
     hdr = plan.hdr[:B].cpu().numpy().astype(np.int64)
     tot = plan.totals.cpu().numpy()
-    moved = int(np.maximum(hdr[:, tim.HDR_N_KEPT] - hdr[:, tim.HDR_KEEP_PAGES] * 16, 0).sum())
+    ps = ctx.cfg.page_size
+    moved = int(np.maximum(hdr[:, tim.HDR_N_KEPT] - hdr[:, tim.HDR_KEEP_PAGES] * ps, 0).sum())
     n_before, n_after = int(hdr[:, tim.HDR_N].sum()), int(hdr[:, tim.HDR_N_KEPT].sum())
-    compact_bytes = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * ctx.cfg.layers
+    # page size 16 reads and writes K and V of every moved token; page size 1 only K, in place
+    compact_bytes = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * ctx.cfg.layers * (1.0 if ps == 16 else 0.5)
     ms_c = float(np.median(t_compact))
+    res_common = {
+        "metric": "flush of all sequences at once: plan + KV compaction (RoPE re-rotation) + commit",
+        "value": round(float(np.median(t_plan)) + ms_c + float(np.median(t_commit)), 3), "unit": "ms per flush call",
+        "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name + "/all-big-flushes", "batch": B, "layers": ctx.cfg.layers, "page_size": ps,
+                   "tokens_before": n_before, "tokens_after": n_after, "prune_ratio": round(1 - n_after / n_before, 4),
+                   "moved_tokens": moved},
+        "plan_ms": round(float(np.median(t_plan)), 3), "compact_ms": round(ms_c, 3),
+        "commit_ms": round(float(np.median(t_commit)), 3),
+        "roofline": {"bound": "hbm", "kernel": "tim_compact_kernel" if ps == 16 else "tim_rotate_inplace_kernel",
+                     "achieved": round(compact_bytes / (ms_c * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(compact_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": compact_bytes}}
+    if ps != 16:                                     # the extend kernel reads 16-token pages only
+        print(json.dumps(res_common), flush=True)
+        return
     # extend attention on the committed plan: every survivor behind the first pruned token re-attends
     n_ext = int(tot[tim.TOT_EXT])
     g = torch.Generator(device="cuda"); g.manual_seed(args.seed + 2)
@@ -214,25 +234,16 @@ def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
     pairs = float(sum((int(mm) * (int(mm) + 1) - int(ff) * (int(ff) + 1)) // 2 for ff, mm in zip(f, m) if mm > ff))
     ext_flops = pairs * shape.q_heads * 128 * 4.0                    # QK and PV, multiply + add, per layer
     ms_e = float(np.median(t_ext))
-    res = {
-        "metric": "flush of all sequences at once: plan + KV compaction (RoPE re-rotation) + commit",
-        "value": round(float(np.median(t_plan)) + ms_c + float(np.median(t_commit)), 3), "unit": "ms per flush call",
-        "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": shape.name + "/all-big-flushes", "batch": B, "layers": ctx.cfg.layers,
-                   "tokens_before": n_before, "tokens_after": n_after, "prune_ratio": round(1 - n_after / n_before, 4),
-                   "moved_tokens": moved, "extended_tokens": n_ext},
-        "plan_ms": round(float(np.median(t_plan)), 3), "compact_ms": round(ms_c, 3),
-        "commit_ms": round(float(np.median(t_commit)), 3),
-        "roofline": {"bound": "hbm", "kernel": "tim_compact_kernel", "achieved": round(compact_bytes / (ms_c * 1e-3) / 1e9, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(compact_bytes / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "bytes_per_launch": compact_bytes},
+    res = dict(res_common)
+    res["config"] = dict(res_common["config"], extended_tokens=n_ext)
+    res.update({
         "extend_attn": {"ms_per_layer": round(ms_e, 3), "ms_all_layers": round(ms_e * ctx.cfg.layers, 2),
                         "roofline": {"bound": "mfma", "kernel": "tim_extend_attn_kernel",
                                      "achieved": round(ext_flops / (ms_e * 1e-3) / 1e12, 1), "peak": 2500.0,
                                      "unit": "TFLOP/s", "frac": round(ext_flops / (ms_e * 1e-3) / 1e12 / 2500.0, 4),
                                      "flops_per_launch": ext_flops},
                         "cost_vs_rerotation": round(ms_e * ctx.cfg.layers / ms_c, 1)},
-    }
+    })
     print(json.dumps(res), flush=True)
 
 
@@ -290,6 +301,8 @@ def main():
                          "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan; "
                          "sweep: the window for pruning-buffer thresholds 0/1/2/4, without pruning, and with the "
                          "in-forward (masking) variant")
+    ap.add_argument("--page-size", type=int, default=16, choices=[16, 1],
+                    help="16 (default) or 1, the paper's own page size: flushes then move no rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
@@ -319,7 +332,7 @@ def main():
     # all sequences flushing at once need all their fresh pages before any old page returns
     headroom = 4096 if args.mode == "window" else 14336
     ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=headroom, layers_alloc=args.layers_alloc,
-                                 seed=args.seed)
+                                 seed=args.seed, page_size=args.page_size)
     plan = tim.Plan(ctx.cfg, args.batch)
     B = args.batch
     g = torch.Generator(device="cuda")
@@ -374,13 +387,14 @@ def main():
     big_ratios = []
     for step, n_ids, hdr in record["hdr"]:
         h = hdr.cpu().numpy().astype(np.int64)
-        mv = np.maximum(h[:, tim.HDR_N_KEPT] - h[:, tim.HDR_KEEP_PAGES] * 16, 0)
+        mv = np.maximum(h[:, tim.HDR_N_KEPT] - h[:, tim.HDR_KEEP_PAGES] * args.page_size, 0)
         moved += int(mv.sum())
         for row in h:
             if row[tim.HDR_N] - row[tim.HDR_N_KEPT] > row[tim.HDR_N] // 2:
                 big_ratios.append(1.0 - row[tim.HDR_N_KEPT] / row[tim.HDR_N])
     bytes_attn = float(attn_bytes_step.sum()) * shape.layers
-    bytes_compact = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * shape.layers
+    # page size 16 copies K and V of every moved token; page size 1 only rewrites K in place
+    bytes_compact = moved * 2.0 * KV_BYTES_PER_TOKEN_LAYER * shape.layers * (1.0 if args.page_size == 16 else 0.5)
     bytes_append = args.steps * B * KV_BYTES_PER_TOKEN_LAYER * shape.layers
     total_bytes = bytes_attn + bytes_compact + bytes_append
     attn_bytes_launch = np.repeat(attn_bytes_step, shape.layers).astype(np.float64)
@@ -396,7 +410,7 @@ def main():
         "achieved_hbm_gbps": round(total_bytes / dt / 1e9, 1),
         "hbm_frac_of_peak": round(total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 4),
         "config": {"workload": shape.name, "batch": B, "layers": shape.layers, "layers_allocated": L_alloc,
-                   "q_heads": shape.q_heads, "kv_heads": shape.kv_heads, "head_dim": 128, "page_size": 16,
+                   "q_heads": shape.q_heads, "kv_heads": shape.kv_heads, "head_dim": 128, "page_size": args.page_size,
                    "threshold": shape.threshold, "positions_per_seq": [int(min(wl.preload)), int(max(wl.preload))],
                    "big_flushes": len(big_ratios),
                    "mean_prune_ratio_big_flush": round(float(np.mean(big_ratios)), 4) if big_ratios else None,
@@ -405,7 +419,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_mfma_kernel",
                      "achieved": round(float(achieved), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(float(achieved) / HBM_PEAK_GBPS, 4),
-                     "traffic": stored_traffic(B, args.steps, args.seed),
+                     "traffic": stored_traffic(B, args.steps, args.seed) if args.page_size == 16 else None,
                      "launches": int(attn_ms.size), "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2),
                      "avg_bytes_per_launch": round(float(attn_bytes_launch.mean()), 1)},
     }
