@@ -247,6 +247,97 @@ def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
     print(json.dumps(res), flush=True)
 
 
+def horizon_mode(torch, tim, np, configs, args):
+    """Configuration 5: 262,144 positions per sequence inside a 32K window.  The integer path
+    (marks, plans, commits, slot reservation) runs for the whole horizon; four 64-step windows
+    along it are timed with all 36 layers (a full-horizon timing would take most of an hour)."""
+    B, horizon, win = min(args.batch, 16), 262144, 64
+    shape, wl = configs.config5(batch=B, horizon=horizon)
+    shape.q_scale = 128 ** -0.5
+    cap_pages = 32768 // args.page_size
+    used_nodes = max(max((node for (p, _, node) in t.marks if p <= horizon), default=0) for t in wl.traces) + 1
+    num_pages = B * cap_pages + 4096 * (16 // args.page_size)
+    per_layer = 2 * num_pages * shape.kv_heads * args.page_size * 128 * 2
+    log(f"[bench] pool: {num_pages} pages x {shape.layers} layers = {per_layer * shape.layers / 1e9:.1f} GB")
+    shp = (shape.layers, num_pages, shape.kv_heads, args.page_size, 128)
+    g = torch.Generator(device="cuda"); g.manual_seed(args.seed)
+    k_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    v_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    for l in range(shape.layers):
+        k_pool[l].normal_(0.0, 1.0, generator=g)
+        v_pool[l].normal_(0.0, 1.0, generator=g)
+    ctx = tim.Context(shape.layers, shape.q_heads, shape.kv_heads, num_pages, B, cap_pages, used_nodes,
+                      page_size=args.page_size, pools=(k_pool, v_pool))
+    plan = tim.Plan(ctx.cfg, B)
+    rnd = lambda *s: torch.randn(*s, generator=g, device="cuda").to(torch.bfloat16)
+    q = [rnd(B, shape.q_heads, 128) for _ in range(shape.layers)]
+    kn = [rnd(B, shape.kv_heads, 128) for _ in range(shape.layers)]
+    vn = [rnd(B, shape.kv_heads, 128) for _ in range(shape.layers)]
+    out = torch.empty(B, shape.q_heads, 128, dtype=torch.bfloat16, device="cuda")
+    dev_i32 = lambda a, shape_=None: torch.tensor(a, dtype=torch.int32, device="cuda")
+
+    def step(s, full):
+        ops = wl.step_ops(s)
+        if ops:
+            ctx.tim_tree_mark(dev_i32(ops).reshape(-1, 4))
+        ids = wl.flush_seqs(s)
+        if ids:
+            ctx.tim_prune_plan(dev_i32(ids), shape.threshold, plan)
+            if full:
+                ctx.tim_kv_compact(plan, 0, shape.layers)
+            ctx.tim_plan_commit(plan)
+        ctx.tim_seq_advance()
+        if full:
+            for layer in range(shape.layers):
+                ctx.tim_kv_append(layer, kn[layer], vn[layer])
+                ctx.tim_decode_attn(layer, q[layer], out, shape.q_scale, 32768)
+        return len(ids)
+
+    starts = [65536 - win, 131072 - win, 196608 - win, horizon - win]
+    at, t_total, tok_total, flushes, attn_ms_all, lens_all = 0, 0.0, 0, 0, [], []
+    t_ff = time.perf_counter()
+    for w0 in starts:
+        while at < w0:                                  # integer path only between the windows
+            step(at, False)
+            at += 1
+        torch.cuda.synchronize()
+        assert ctx.tim_status() == 0
+        lens0 = ctx.seq_len.cpu().numpy().astype(np.int64)
+        ctx.tim_timing_begin(win * shape.layers)
+        t0 = time.perf_counter()
+        lens_w = []
+        for s in range(w0, w0 + win):
+            flushes += step(s, True)
+            lens_w.append(ctx.seq_len.clone())
+        torch.cuda.synchronize()
+        t_total += time.perf_counter() - t0
+        attn_ms_all += ctx.tim_timing_end()
+        lens_all += [x.cpu().numpy().astype(np.int64) for x in lens_w]
+        at = w0 + win
+        log(f"[bench] window at {w0}: live {lens0.min()}..{lens0.max()} tokens")
+    assert ctx.tim_status() == 0
+    lens = np.stack(lens_all)
+    assert lens.max() < 32768
+    attn_ms = np.array(attn_ms_all)
+    attn_bytes = np.repeat(lens.sum(axis=1) * KV_BYTES_PER_TOKEN_LAYER, shape.layers).astype(np.float64)
+    achieved = attn_bytes.sum() / (attn_ms.sum() * 1e-3) / 1e9
+    n_steps = len(starts) * win
+    res = {"metric": METRIC, "value": round(n_steps / t_total, 3), "unit": "decode steps/s", "n_gpus": 1,
+           "steps": n_steps, "warmup": 0, "ms_per_step": round(1e3 * t_total / n_steps, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "tokens_per_s": round(n_steps / t_total * B, 1),
+           "config": {"workload": shape.name, "batch": B, "layers": shape.layers, "page_size": args.page_size,
+                      "horizon_positions": horizon, "timed_windows": [[w, win] for w in starts],
+                      "integer_path_steps": horizon, "integer_path_seconds": round(time.perf_counter() - t_ff - t_total, 1),
+                      "max_live_tokens": int(lens.max()), "mean_live_tokens": round(float(lens.mean()), 1),
+                      "flushed_sequences_in_windows": flushes},
+           "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_mfma_kernel", "achieved": round(float(achieved), 1),
+                        "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(float(achieved) / HBM_PEAK_GBPS, 4),
+                        "traffic": None, "launches": int(attn_ms.size),
+                        "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2)}}
+    print(json.dumps(res), flush=True)
+
+
 def sweep_mode(torch, tim, np, ctx, plan, shape, wl, staged, initial, args):
     """Synthetic analogue of the paper's throughput-vs-pruning-buffer figure: the same window
     with thresholds 0/1/2/4 under flush-by-compaction and under in-forward masking, and
@@ -301,6 +392,8 @@ def main():
                          "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan; "
                          "sweep: the window for pruning-buffer thresholds 0/1/2/4, without pruning, and with the "
                          "in-forward (masking) variant")
+    ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
+                    help="config3 is the headline workload; the others are reported for the record")
     ap.add_argument("--page-size", type=int, default=16, choices=[16, 1],
                     help="16 (default) or 1, the paper's own page size: flushes then move no rows")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -327,10 +420,24 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     t_setup = time.perf_counter()
-    shape, wl = configs.config3(batch=args.batch, steps=max(args.steps, args.warmup), seed=args.seed)
+    if args.workload == "config5":
+        horizon_mode(torch, tim, np, configs, args)
+        return
+    if args.workload == "config2":
+        args.batch, args.steps = 1, min(args.steps, 64)
+        shape, wl = configs.config2(steps=args.steps)
+        headroom = 2304
+    elif args.workload == "config4":
+        args.batch = min(args.batch, 32)
+        shape, wl = configs.config4(batch=args.batch, steps=args.steps)
+        headroom = (args.batch * 512) // 4                  # 25 % over the pages in use: they really recycle
+        # the configuration allows one layer pool timed 36 times; all 36 layers fit (38 GB), so they are real
+    else:
+        shape, wl = configs.config3(batch=args.batch, steps=max(args.steps, args.warmup), seed=args.seed)
+        # all sequences flushing at once need all their fresh pages before any old page returns
+        headroom = 4096 if args.mode == "window" else 14336
+    args.warmup = min(args.warmup, args.steps)
     shape.q_scale = 128 ** -0.5
-    # all sequences flushing at once need all their fresh pages before any old page returns
-    headroom = 4096 if args.mode == "window" else 14336
     ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=headroom, layers_alloc=args.layers_alloc,
                                  seed=args.seed, page_size=args.page_size)
     plan = tim.Plan(ctx.cfg, args.batch)
@@ -367,14 +474,24 @@ def main():
     assert ctx.tim_status() == 0
     for n, t in initial.items():                    # rewind the integer state; K/V content stays random
         getattr(ctx, n).copy_(t)
+    # pass A: the timed region proper, exactly K steps, nothing but the path's own calls
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, None)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert ctx.tim_status() == 0
+    # pass B: the same K steps again from the same state, instrumented: HIP events ride on the dispatch
+    # of every attention main kernel (on the launch stream), lengths and plan headers are logged
+    for n, t in initial.items():
+        getattr(ctx, n).copy_(t)
     record = dict(hdr=[], lens=torch.zeros(args.steps, B, dtype=torch.int32, device="cuda"))
-    # HIP events ride on the dispatch of every attention main kernel (on the launch stream)
     ctx.tim_timing_begin(args.steps * shape.layers)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, record)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_instrumented = time.perf_counter() - t0
     attn_ms = np.array(ctx.tim_timing_end(), dtype=np.float64)
     assert attn_ms.size == args.steps * shape.layers
     status = ctx.tim_status()
@@ -383,10 +500,13 @@ def main():
     # ---- accounting (host, after the clock stopped) ----
     lens = record["lens"].cpu().numpy().astype(np.int64)            # [steps][B], lengths attended
     attn_bytes_step = lens.sum(axis=1) * KV_BYTES_PER_TOKEN_LAYER   # per layer launch
-    moved = pruned_n = pruned_m = 0
+    moved = pages_popped = pages_pushed = max_shift = 0
     big_ratios = []
     for step, n_ids, hdr in record["hdr"]:
         h = hdr.cpu().numpy().astype(np.int64)
+        pages_popped += int(h[:, tim.HDR_NEED].sum())
+        pages_pushed += int(h[:, tim.HDR_PUSH].sum())
+        max_shift = max(max_shift, int((h[:, tim.HDR_N] - h[:, tim.HDR_N_KEPT]).max()))
         mv = np.maximum(h[:, tim.HDR_N_KEPT] - h[:, tim.HDR_KEEP_PAGES] * args.page_size, 0)
         moved += int(mv.sum())
         for row in h:
@@ -406,7 +526,7 @@ def main():
         "metric": METRIC, "value": round(steps_per_s, 3), "unit": "decode steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * dt / args.steps, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "tokens_per_s": round(steps_per_s * B, 1),
+        "tokens_per_s": round(steps_per_s * B, 1), "ms_per_step_instrumented_replay": round(1e3 * dt_instrumented / args.steps, 4),
         "achieved_hbm_gbps": round(total_bytes / dt / 1e9, 1),
         "hbm_frac_of_peak": round(total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 4),
         "config": {"workload": shape.name, "batch": B, "layers": shape.layers, "layers_allocated": L_alloc,
@@ -414,12 +534,15 @@ def main():
                    "threshold": shape.threshold, "positions_per_seq": [int(min(wl.preload)), int(max(wl.preload))],
                    "big_flushes": len(big_ratios),
                    "mean_prune_ratio_big_flush": round(float(np.mean(big_ratios)), 4) if big_ratios else None,
-                   "moved_tokens": moved, "mean_live_tokens_per_seq": round(float(lens.mean()), 1),
+                   "moved_tokens": moved, "flush_calls": len(record["hdr"]),
+                   "pages_popped_by_flushes": pages_popped, "pages_pushed_by_flushes": pages_pushed,
+                   "max_position_shift": max_shift, "mean_live_tokens_per_seq": round(float(lens.mean()), 1),
                    "bytes_per_step_GB": round(total_bytes / args.steps / 1e9, 3)},
         "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_mfma_kernel",
                      "achieved": round(float(achieved), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(float(achieved) / HBM_PEAK_GBPS, 4),
-                     "traffic": stored_traffic(B, args.steps, args.seed) if args.page_size == 16 else None,
+                     "traffic": stored_traffic(B, args.steps, args.seed)
+                     if (args.page_size == 16 and args.workload == "config3") else None,
                      "launches": int(attn_ms.size), "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2),
                      "avg_bytes_per_launch": round(float(attn_bytes_launch.mean()), 1)},
     }

@@ -8,7 +8,7 @@ from typing import Dict, List
 
 from .rng import Stream
 from .schedule import Workload, every
-from .tree import TreeSpec, generate
+from .tree import MARK_SUB_END, TreeSpec, generate
 
 
 @dataclass
@@ -25,6 +25,7 @@ SPEC_C1 = TreeSpec(depth_max=4, branch=(1, 4), thought=(16, 128), concl=(8, 32))
 SPEC_C2 = TreeSpec(depth_max=6, branch=(2, 5), thought=(32, 512), concl=(16, 64))
 SPEC_C3 = TreeSpec(depth_max=6, branch=(2, 5), thought=(32, 256), concl=(16, 64))
 SPEC_C4 = TreeSpec(depth_max=10, branch=(2, 3), thought=(16, 64), concl=(8, 16))
+SPEC_C5 = TreeSpec(depth_max=8, branch=(2, 6), thought=(32, 1024), concl=(32, 1024))
 
 
 def config3(batch: int = 64, steps: int = 256, seed: int = 1000, lo: int = 16384, hi: int = 32768,
@@ -50,3 +51,35 @@ def config2(steps: int = 64, seed: int = 3):
     p0 = 32768 - steps
     wl = Workload([generate(seed, p0 + steps + 1, SPEC_C2)], [p0], steps, every(8, steps, 1))
     return shape, wl
+
+
+def config4(batch: int = 32, steps: int = 256, seed: int = 4000):
+    """Prune-heavy stress: deep narrow trees of 8K positions, a pruning buffer of two lists,
+    every sequence flushed every 2 steps; one layer pool timed 36 times per step."""
+    shape = Shape(36, 32, 8, 2, 1.0, "config4-prune-heavy")
+    p0 = 8192 - steps
+    traces = [generate(seed + b, p0 + steps + 1, SPEC_C4) for b in range(batch)]
+    return shape, Workload(traces, [p0] * batch, steps, every(2, steps, batch))
+
+
+def config5(batch: int = 16, horizon: int = 262144, seed: int = 5000, cadence: int = 8):
+    """Beyond-context horizon: every sequence generates `horizon` positions while its working
+    memory stays below 32K.  A sequence is flushed at the next multiple of `cadence` steps
+    after one of its subtask lists completed (bookkeeping on the marks only)."""
+    shape = Shape(36, 32, 8, 2, 1.0, "config5-beyond-context")
+    traces = [generate(seed + b, horizon + 2, SPEC_C5) for b in range(batch)]
+    done_at = []
+    for tr in traces:
+        steps_with_completion = sorted({p for (p, code, _) in tr.marks if code == MARK_SUB_END and p < horizon})
+        done_at.append(steps_with_completion)
+    flush: Dict[int, List[int]] = {}
+    for b, pts in enumerate(done_at):
+        for p in pts:
+            s = ((p + cadence - 1) // cadence) * cadence       # marks at boundary p are seen at step p
+            if s < horizon:
+                ids = flush.setdefault(s, [])
+                if b not in ids:
+                    ids.append(b)
+    for s in flush:
+        flush[s].sort()
+    return shape, Workload(traces, [0] * batch, horizon, flush)
