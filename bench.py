@@ -121,11 +121,12 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
         hint = hint_len + (step - hint_step) + 1
         for layer in range(layers_run):
             la = layer % L_alloc
-            ctx.tim_kv_append(la, staged["k_new"][layer], staged["v_new"][layer])
             if flush_kind == "mask":
+                ctx.tim_kv_append(la, staged["k_new"][layer], staged["v_new"][layer])
                 ctx.tim_decode_attn_masked(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
-            else:
-                ctx.tim_decode_attn(la, staged["q"][layer], staged["out"], shape.q_scale, hint)
+            else:                                   # append and attention of the layer in one launch
+                ctx.tim_decode_attn_append(la, staged["q"][layer], staged["k_new"][layer], staged["v_new"][layer],
+                                           staged["out"], shape.q_scale, hint)
         host = staged["pinned"][step % len(staged["pinned"])]
         host.copy_(ctx.seq_len, non_blocking=True)
         ev = torch.cuda.Event()
@@ -289,8 +290,7 @@ def horizon_mode(torch, tim, np, configs, args):
         ctx.tim_seq_advance()
         if full:
             for layer in range(shape.layers):
-                ctx.tim_kv_append(layer, kn[layer], vn[layer])
-                ctx.tim_decode_attn(layer, q[layer], out, shape.q_scale, 32768)
+                ctx.tim_decode_attn_append(layer, q[layer], kn[layer], vn[layer], out, shape.q_scale, 32768)
         return len(ids)
 
     starts = [65536 - win, 131072 - win, 196608 - win, horizon - win]

@@ -275,6 +275,14 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
                     int32_t max_seq_len, tim_stream stream);
 
 /*
+ * tim_kv_append and tim_decode_attn of one layer in a single launch: the wave that reads a
+ * sequence's last page takes the pending token's row from k_new / v_new (same layout as in
+ * tim_kv_append), uses it, and stores it into the pool.  Results are those of the two calls.
+ */
+int tim_decode_attn_append(tim_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
+                           float sm_scale, int32_t out_dtype, int32_t max_seq_len, tim_stream stream);
+
+/*
  * Attention half of the paper's own repositioning (Eq. 1, f_extend): after a flush is
  * committed, every survivor behind the first pruned token of a flushed sequence is
  * "extended", i.e. attends causally to the untouched prefix, the earlier extended tokens

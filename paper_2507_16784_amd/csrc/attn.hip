@@ -104,7 +104,8 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
-                        void *__restrict__ out, float scale_log2, int cpb) {
+                        void *__restrict__ out, float scale_log2, int cpb, const uint4 *__restrict__,
+                        const uint4 *__restrict__) {
   __shared__ float red_m[AT_WAVES * 4][TIM_G];
   __shared__ float red_l[AT_WAVES * 4][TIM_G];
   __shared__ float red_o[AT_WAVES * 4][TIM_G][TIM_D];
@@ -257,7 +258,8 @@ __device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __bui
 template <bool OUT_BF16, bool MASKED, bool PS1>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
-                             void *__restrict__ out, float scale_log2, int cpb) {
+                             void *__restrict__ out, float scale_log2, int cpb, const uint4 *__restrict__ k_new,
+                             const uint4 *__restrict__ v_new) {
   __shared__ float red_m[AT_WAVES][TIM_G];
   __shared__ float red_l[AT_WAVES][TIM_G];
   __shared__ float red_o[AT_WAVES][TIM_G][TIM_D];
@@ -353,6 +355,43 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         for (int i = 0; i < 4; ++i) va[i] = vpool[tile_a + (4 * g + i) * 16 + j];
 #pragma unroll
         for (int i = 0; i < 4; ++i) vb[i] = vpool[tile_b + (4 * g + i) * 16 + j];
+      }
+
+      // fused append: the wave that owns the sequence's last page takes the pending token's
+      // row from the caller's buffers instead of the pool, and stores it into the pool
+      if (k_new != nullptr) {
+        const int last_tok = n - 1, last_pg = last_tok / TIM_PS, row = last_tok % TIM_PS;
+        if (pg == last_pg || (has_b && pg + 1 == last_pg)) {  // uniform for the wave
+          const bool in_b = pg != last_pg;
+          int64_t krow, vrow;  // 16-byte units of the row's start in the pools
+          if (PS1) {
+            int sid = ptab[last_tok];
+            if (sid < 0 || sid >= cfg.num_pages) sid = 0;  // reported by the loads above
+            krow = vrow = ((layer_base + sid) * cfg.kv_heads + kvh) * 16;
+          } else {
+            int phys = __builtin_amdgcn_readlane(my_pid, last_pg - pg0);
+            if (phys < 0 || phys >= cfg.num_pages) phys = 0;
+            krow = vrow = ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16) + row * 16;
+          }
+          const int64_t src = ((int64_t)b * cfg.kv_heads + kvh) * 16;
+          if (j == row) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+              const uint4 x = k_new[src + 4 * s + g];
+              if (in_b) kb[s] = x; else ka[s] = x;
+              const_cast<uint4 *>(kpool)[krow + 4 * s + g] = x;
+            }
+          }
+          if ((row >> 2) == g) {
+            const uint4 x = v_new[src + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (i == (row & 3)) {
+                if (in_b) vb[i] = x; else va[i] = x;
+              }
+            const_cast<uint4 *>(vpool)[vrow + j] = x;
+          }
+        }
       }
 
       // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
@@ -517,19 +556,21 @@ extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
 
 template <int IMPL, bool OUT_BF16>  // 0 = vector ALU, 1 = matrix cores, 2 = matrix cores with visibility mask
 static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
-                      float scale_log2, int cpb) {
+                      float scale_log2, int cpb, const void *k_new, const void *v_new) {
   const bool ps1 = ctx->cfg.page_size == 1;
   auto kernel = IMPL == 2   ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, true, true> : tim_attn_partial_mfma_kernel<OUT_BF16, true, false>)
                 : IMPL == 1 ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false, true> : tim_attn_partial_mfma_kernel<OUT_BF16, false, false>)
                             : tim_attn_partial_kernel<OUT_BF16>;
   const uint4 *q4 = reinterpret_cast<const uint4 *>(q);
+  const uint4 *kn = reinterpret_cast<const uint4 *>(k_new), *vn = reinterpret_cast<const uint4 *>(v_new);
   if (ctx->timing_on && ctx->timing_n < (int)ctx->ev_start.size()) {
     // events attached to the dispatch itself: the kernel's own begin/end, no extra barrier
     const int i = ctx->timing_n++;
     hipExtLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->ev_start[i], ctx->ev_stop[i], 0, ctx->cfg, ctx->st,
-                          ws, layer, q4, out, scale_log2, cpb);
+                          ws, layer, q4, out, scale_log2, cpb, kn, vn);
   } else {
-    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb);
+    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb, kn,
+                       vn);
   }
 }
 
@@ -567,7 +608,8 @@ extern "C" int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out) {
 }
 
 static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
-                     int32_t max_seq_len, tim_stream stream, bool masked) {
+                     int32_t max_seq_len, tim_stream stream, bool masked, const void *k_new = nullptr,
+                     const void *v_new = nullptr) {
   if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers ||
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask) ||
       (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
@@ -580,7 +622,7 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
   const int rows = cfg.max_batch * cfg.kv_heads;
   // chunks per block: as many as still leave enough blocks to fill the chip several times
   int cpb = ctx->attn_cpb;
-  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < 8 * (int64_t)ctx->n_cu) --cpb;
+  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < ctx->attn_fill * (int64_t)ctx->n_cu) --cpb;
   int slots = (nchunks + cpb - 1) / cpb;
   if (slots > AT_MAX_SLOTS) slots = AT_MAX_SLOTS;
   if (slots < 1) slots = 1;
@@ -592,14 +634,14 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
   dim3 grid(cfg.max_batch * cfg.kv_heads, slots);
   const bool bf = out_dtype == TIM_OUT_BF16;
   if (masked) {
-    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
-    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
   } else if (ctx->attn_impl == 1) {
-    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
-    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
   } else {
-    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
-    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb);
+    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
   }
   TIM_LAUNCH_CHECK();
   if (slots > 1) {  // with one slot every block has already written its final output
@@ -619,4 +661,16 @@ extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void 
 extern "C" int tim_decode_attn_masked(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
                                       int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
   return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, true);
+}
+
+extern "C" int tim_decode_attn_append(tim_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                      void *out, float sm_scale, int32_t out_dtype, int32_t max_seq_len,
+                                      tim_stream stream) {
+  if (!k_new || !v_new) return TIM_ERR_INVALID_ARG;
+  if (ctx && ctx->bound && ctx->attn_impl != 1) {  // the vector-ALU variant has no fused path: two launches
+    const int rc = tim_kv_append(ctx, layer, k_new, v_new, stream);
+    if (rc != TIM_OK) return rc;
+    return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, false);
+  }
+  return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, false, k_new, v_new);
 }

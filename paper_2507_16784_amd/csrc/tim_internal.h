@@ -21,6 +21,7 @@ struct tim_ctx {
   int n_cu;
   int attn_impl;  // 1 = matrix-core attention (default), 0 = vector-ALU attention
   int attn_cpb;   // target chunks per attention block
+  int attn_fill;  // shrink blocks until there are this many per CU
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
   int timing_n = 0;

@@ -22,7 +22,7 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_seq_extend", "tim_kv_write", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_decode_attn", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
+           "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
 class tim_config(C.Structure):
@@ -66,6 +66,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_kv_compact": (C.c_int, [p, C.POINTER(tim_plan), i32, i32, p]),
         "tim_plan_commit": (C.c_int, [p, C.POINTER(tim_plan), p]),
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
+        "tim_decode_attn_append": (C.c_int, [p, i32, p, p, p, p, f32, i32, i32, p]),
         "tim_decode_attn_masked": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_prune_mask": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
         "tim_extend_attn": (C.c_int, [p, i32, C.POINTER(tim_plan), p, p, i32, f32, i32, p]),
@@ -234,6 +235,18 @@ class Context:
         od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
         _check(lib().tim_decode_attn(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len, _stream()),
                "tim_decode_attn")
+
+    def tim_decode_attn_append(self, layer: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                               out: torch.Tensor, sm_scale: float, max_seq_len: int = 0):
+        assert q.dtype == torch.bfloat16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim) == tuple(out.shape)
+        assert out.is_cuda and out.is_contiguous() and out.dtype in (torch.float32, torch.bfloat16)
+        for t in (k_new, v_new):
+            assert t.dtype == torch.bfloat16 and t.is_cuda and t.is_contiguous()
+            assert tuple(t.shape) == (self.cfg.max_batch, self.cfg.kv_heads, self.cfg.head_dim)
+        od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+        _check(lib().tim_decode_attn_append(self.handle, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), sm_scale,
+                                            od, max_seq_len, _stream()), "tim_decode_attn_append")
 
     def tim_prune_mask(self, seq_ids: torch.Tensor, threshold: int, plan: Plan):
         assert seq_ids.dtype == torch.int32 and seq_ids.is_cuda and seq_ids.is_contiguous()

@@ -34,6 +34,8 @@ class GpuRuntime:
         self.plan = tim.Plan(self.ctx.cfg, max_flush_seqs or cfg.max_batch)
         self.dev = self.ctx.seq_len.device
         self.max_len_hint = 0
+        self.fused_append = False      # True: append + attention of a layer go out as one call
+        self._pending = {}
 
     # ---- inputs ------------------------------------------------------------------
     def _i32(self, a):
@@ -67,6 +69,7 @@ class GpuRuntime:
             self.ctx.tim_tree_mark(self._i32(np.asarray(ops, dtype=np.int32).reshape(-1, 4)))
 
     def advance(self):
+        self._settle()
         self.ctx.tim_seq_advance()
 
     def extend_seq(self, counts):
@@ -77,9 +80,19 @@ class GpuRuntime:
         self.ctx.tim_kv_write(layer, self._i32(off), self._bf16(k_rows_bits), self._bf16(v_rows_bits))
 
     def append(self, layer, k_new_bits, v_new_bits):
-        self.ctx.tim_kv_append(layer, self._bf16(k_new_bits), self._bf16(v_new_bits))
+        if self.fused_append:
+            self._pending[layer] = (self._bf16(k_new_bits), self._bf16(v_new_bits))
+        else:
+            self.ctx.tim_kv_append(layer, self._bf16(k_new_bits), self._bf16(v_new_bits))
+
+    def _settle(self):
+        """Rows stashed for a fused call that never came (a step without attention) are appended plainly."""
+        for layer, (k, v) in self._pending.items():
+            self.ctx.tim_kv_append(layer, k, v)
+        self._pending = {}
 
     def prune_plan(self, seq_ids):
+        self._settle()
         ids = self._i32(sorted(seq_ids))
         self.ctx.tim_prune_plan(ids, self.threshold, self.plan)
         self._n_flush = len(seq_ids)
@@ -96,7 +109,11 @@ class GpuRuntime:
 
     def decode_attn(self, layer, q_bits, sm_scale, out_dtype=torch.float32):
         out = torch.empty((self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim), dtype=out_dtype, device=self.dev)
-        self.ctx.tim_decode_attn(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
+        if layer in self._pending:
+            k, v = self._pending.pop(layer)
+            self.ctx.tim_decode_attn_append(layer, self._bf16(q_bits), k, v, out, sm_scale, self.max_len_hint)
+        else:
+            self.ctx.tim_decode_attn(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
         return out.float().cpu().numpy()
 
     def prune_mask(self, seq_ids):
@@ -121,6 +138,7 @@ class GpuRuntime:
 
     # ---- read back ---------------------------------------------------------------------
     def state(self):
+        self._settle()
         c = self.ctx
         top = int(c.free_top.item())
         return dict(page_table=c.page_table.cpu().numpy(), seq_len=c.seq_len.cpu().numpy(),
@@ -131,6 +149,7 @@ class GpuRuntime:
                     lists_done=c.lists_done.cpu().numpy())
 
     def gather_kv(self, layer, b):
+        self._settle()
         c = self.ctx
         n = int(c.seq_len[b].item())
         t = torch.arange(n, device=self.dev)

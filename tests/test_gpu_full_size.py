@@ -111,8 +111,7 @@ def test_config3_full_size_sampled():
         hint = int(ora.seq_len.max())
         for layer in ([0, 17, 35] if step in (0, 5, 9) else [step % 36]):
             q, kn, vn = rnd(64, 32, 128), rnd(64, 8, 128), rnd(64, 8, 128)
-            ctx.tim_kv_append(layer, kn, vn)
-            ctx.tim_decode_attn(layer, q, out, shape.q_scale, hint)
+            ctx.tim_decode_attn_append(layer, q, kn, vn, out, shape.q_scale, hint)     # as bench.py launches it
             got = out.cpu().numpy()
             for b in {0, 1, 2, 63, 31} if step in (0, 5, 9) else {big.get(step, 40)}:
                 kb, vb = _gather(ctx, layer, b)

@@ -140,10 +140,11 @@ def check_kv(ora, gpu, drift_ok=False):
     assert same >= 0.99 * tot
 
 
-def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1):
+def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1, fused=False):
     ora = OracleRuntime(cfg, threshold)
     harness.preload_oracle(ora, wl, seed, kv_scale)
     gpu = gb.GpuRuntime(cfg, threshold)
+    gpu.fused_append = fused
     gb.preload_gpu(gpu, wl, seed, kv_scale)
     check_state(ora, gpu)
     check_kv(ora, gpu)
@@ -472,3 +473,21 @@ def test_page_size_one_config1_and_config2_shapes(gb):
     wl = Workload([generate(3, p0 + steps + 1, SPEC_C2)], [p0], steps, every(8, steps, 1))
     cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=64, page_size=1)
     replay(gb, wl, cfg, 1, 3, 1.0, 128 ** -0.5, attend_every=4)
+
+
+@pytest.mark.parametrize("page_size", [16, 1])
+def test_fused_append_and_attention(gb, page_size):
+    """tim_decode_attn_append: one launch per layer; pool contents and outputs as with two calls."""
+    seeds, p0s, steps = [81, 82, 83, 84], [15, 16, 31, 200], 70
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(6, steps, 4))
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=40 * (16 // page_size),
+                              page_size=page_size)
+    replay(gb, wl, cfg, 1, 8, 1.0, 128 ** -0.5, fused=True)
+    # larger, 32/8 heads, ragged lengths around chunk boundaries
+    p0s = [255, 256, 257, 1023, 4111]
+    traces = [generate(90 + i, p + 20, SPEC_C1) for i, p in enumerate(p0s)]
+    wl = Workload(traces, p0s, 18, every(5, 18, 5))
+    cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=300 * (16 // page_size),
+                              page_size=page_size)
+    replay(gb, wl, cfg, 0, 9, 128 ** -0.5, 128 ** -0.5, fused=True)
