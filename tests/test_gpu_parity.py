@@ -491,3 +491,36 @@ def test_fused_append_and_attention(gb, page_size):
     cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=300 * (16 // page_size),
                               page_size=page_size)
     replay(gb, wl, cfg, 0, 9, 128 ** -0.5, 128 ** -0.5, fused=True)
+
+
+def test_wide_batch_exceeds_one_scan_pass(gb):
+    """1,300 sequences: the slot-reservation and page-plan scans loop over more sequences than
+    one block has threads, and a flush lists more than 1,024 sequences."""
+    nseq, steps = 1300, 12
+    rs = np.random.default_rng(3)
+    p0s = [int(x) for x in rs.integers(1, 60, nseq)]
+    base = [generate(500 + i, 90, SPEC_TINY) for i in range(16)]
+    traces = [base[i % 16] for i in range(nseq)]
+    wl = Workload(traces, p0s, steps, {3: list(range(nseq)), 9: list(range(0, nseq, 3))})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=3000)
+    replay(gb, wl, cfg, 0, 11, 1.0, 128 ** -0.5, attend_every=6, kv_check_every=1, fused=True)
+
+
+def test_one_sequence_longer_than_the_slot_cap(gb):
+    """40,000 tokens in one sequence: more 256-token chunks than attention slots, so blocks stride."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    n = 40000
+    tr = Trace(n + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr], [n], 2, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=4)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 2, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    gb.preload_gpu(gpu, wl, 2, 1.0)
+    for step in range(2):
+        gpu.fused_append = step == 1
+        want = harness.run_step(ora, wl, step, 2, 1.0, 128 ** -0.5)
+        got = harness.run_step(gpu, wl, step, 2, 1.0, 128 ** -0.5)
+        check_attention(got[0], want[0])
+    check_state(ora, gpu)
+    assert gpu.status() == 0
