@@ -137,8 +137,9 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
 
 
 def cpu_baseline(shape, seed):
-    """The oracle, as it stands, on a bounded sample of the same workload: 4 sequences of the
-    configuration-3 recipe, 1 layer, their big flush and 8 decode steps; scaled to whole steps."""
+    """The oracle, as it stands, on a bounded sample of the same workload: 32 sequences of the
+    configuration-3 recipe, 1 layer: 3 decode steps on their long working memories, their big
+    flush, then 12 decode steps on what is left; scaled to whole steps."""
     import numpy as np
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import harness
@@ -149,28 +150,31 @@ def cpu_baseline(shape, seed):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = 1
-    nseq, steps = 4, 8
-    _, wl = configs.config3(batch=nseq, steps=steps, seed=seed, stride=0, cadence=10**6)
-    cfg = harness.make_config(wl, layers=1, q_heads=shape.q_heads, kv_heads=shape.kv_heads, headroom_pages=1200)
+    nseq, before, after = 32, 3, 12
+    _, wl = configs.config3(batch=nseq, steps=before + after, seed=seed, stride=0, cadence=10**6)
+    cfg = harness.make_config(wl, layers=1, q_heads=shape.q_heads, kv_heads=shape.kv_heads, headroom_pages=12000)
     rt = OracleRuntime(cfg, shape.threshold)
     harness.preload_oracle(rt, wl, seed, shape.kv_scale)
     q, k, v = harness.step_inputs(seed, 0, cfg, shape.kv_scale)
-    t0 = time.perf_counter()
-    rt.mark(wl.step_ops(0))
-    ev = rt.prune_plan(list(range(nseq)))
-    rt.kv_compact(ev, 0, 1)
-    rt.commit(ev)
-    t_event = (time.perf_counter() - t0) / nseq              # per sequence-layer flush
-    live_tokens = 0
-    t0 = time.perf_counter()
-    for s in range(steps):
+    live_tokens, t_attn, t_event = 0, 0.0, 0.0
+    for s in range(before + after):
+        rt.mark(wl.step_ops(s))
+        if s == before:
+            t0 = time.perf_counter()
+            ev = rt.prune_plan(list(range(nseq)))
+            rt.kv_compact(ev, 0, 1)
+            rt.commit(ev)
+            t_event = (time.perf_counter() - t0) / nseq          # per sequence-layer flush
+        t0 = time.perf_counter()
         rt.advance()
         rt.append(0, k[0], v[0])
         rt.decode_attn(0, q[0], shape.q_scale)
+        t_attn += time.perf_counter() - t0
         live_tokens += int(rt.seq_len.sum())
-    t_tok = (time.perf_counter() - t0) / live_tokens           # per live token-layer of attention
-    return dict(t_event_seq_layer=t_event, t_attn_token_layer=t_tok, threads=threads,
-                sample=f"{nseq} sequences x 1 layer of configuration 3: their big flush + {steps} decode steps")
+    return dict(t_event_seq_layer=t_event, t_attn_token_layer=t_attn / live_tokens, threads=threads,
+                seconds=round(t_attn + t_event * nseq, 1),
+                sample=f"{nseq} sequences x 1 layer of configuration 3: {before} decode steps before their big flush, "
+                       f"the flush, {after} decode steps after")
 
 
 def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
@@ -561,7 +565,7 @@ def main():
         t_step = (float(lens.sum(axis=1).mean()) * shape.layers * cb["t_attn_token_layer"]
                   + big_per_step * shape.layers * cb["t_event_seq_layer"])
         res["cpu_baseline"] = {"value": round(1.0 / t_step, 6), "unit": "decode steps/s", "cores": cb["threads"],
-                               "kind": "oracle", "sample": cb["sample"] +
+                               "kind": "oracle", "sample_seconds": cb["seconds"], "sample": cb["sample"] +
                                "; per-token-layer and per-flush-layer times scaled to the timed window (extrapolated)"}
     print(json.dumps(res), flush=True)
 
