@@ -234,6 +234,8 @@ __global__ void tim_plan_commit_kernel(tim_config cfg, tim_state st, tim_plan pl
   const int e = blockIdx.y;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (!pl.totals[TIM_TOT_OK]) return;
+  // the new stack height is written once, whatever becomes of the first listed sequence
+  if (e == 0 && i == 0) *st.free_top = pl.totals[TIM_TOT_TOP_AFTER_POP] + pl.totals[TIM_TOT_PUSH];
   const int32_t *hdr = pl.hdr + (int64_t)e * TIM_PLAN_HDR;
   if (hdr[TIM_HDR_BAD]) return;
   const int b = hdr[TIM_HDR_SEQ], n = hdr[TIM_HDR_N], m = hdr[TIM_HDR_N_KEPT];
@@ -267,7 +269,6 @@ __global__ void tim_plan_commit_kernel(tim_config cfg, tim_state st, tim_plan pl
     }
   }
   if (i == 0) st.seq_len[b] = m;
-  if (e == 0 && i == 0) *st.free_top = pl.totals[TIM_TOT_TOP_AFTER_POP] + pl.totals[TIM_TOT_PUSH];
 }
 
 // In-forward variant: same rule, but the evicted tokens are only made invisible.  One block

@@ -28,10 +28,6 @@ struct tim_ctx {
   std::vector<hipEvent_t> ev_start, ev_stop;
 };
 
-struct RopeFreq {
-  double f[TIM_D / 2];
-};
-
 #define TIM_HIP_CHECK(expr)                  \
   do {                                       \
     hipError_t _e = (expr);                  \

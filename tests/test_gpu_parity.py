@@ -524,3 +524,55 @@ def test_one_sequence_longer_than_the_slot_cap(gb):
         check_attention(got[0], want[0])
     check_state(ora, gpu)
     assert gpu.status() == 0
+
+
+def test_malformed_tree_and_bad_sequence_list_are_rejected_without_damage(gb):
+    """Device-side validation: a list whose end lies before its begin, or beyond the sequence,
+    sets TIM_ERR_BAD_TREE and leaves that sequence exactly as it was while the other sequence
+    of the same flush is processed; a sequence list that is not ascending sets
+    TIM_ERR_INVALID_ARG.  Every kernel exits normally."""
+    from paper_2507_16784_amd import tim
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    tr = Trace(400, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr], [100, 120], 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=16, max_nodes=4)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 1, 1.0)
+    gb.preload_gpu(gpu, wl, 1, 1.0)
+    good = [(1, MARK_OPEN, 0, 0), (1, MARK_SUB_BEGIN, 0, 10), (1, MARK_SUB_END, 0, 50)]
+    bad = [(0, MARK_OPEN, 0, 0), (0, MARK_SUB_BEGIN, 0, 60), (0, MARK_SUB_END, 0, 20)]       # ends before it begins
+    ora.mark(good)
+    gpu.mark(good + bad)
+    before = gpu.state()
+    kv0 = gpu.gather_kv(0, 0)
+    ev = ora.prune_plan([1]); ora.kv_compact(ev, 0, 1); ora.commit(ev)
+    pl = gpu.prune_plan([0, 1]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    assert gpu.status() == tim.ERR_BAD_TREE
+    after = gpu.state()
+    assert after["seq_len"][0] == 100 and np.array_equal(after["page_table"][0], before["page_table"][0])
+    assert np.array_equal(gpu.gather_kv(0, 0)[0], kv0[0])
+    assert after["seq_len"][1] == ora.seq_len[1] == 80 and np.array_equal(after["page_table"][1], ora.page_table[1])
+    assert np.array_equal(after["free_ids"], ora.free.free_ids())
+    k1o, v1o = ora.gather_kv(0, 1)
+    k1g, v1g = gpu.gather_kv(0, 1)
+    assert np.array_equal(v1g, v1o)
+    check_rotated(k1g, k1o)
+    # a list that reaches beyond the sequence
+    gpu.mark([(0, MARK_SUB_BEGIN, 0, 20), (0, MARK_SUB_END, 0, 60)])                         # repaired ...
+    gpu.mark([(0, MARK_OPEN, 1, 0), (0, MARK_SUB_BEGIN, 1, 90), (0, MARK_SUB_END, 1, 130)])   # ... and broken again
+    pl = gpu.prune_plan([0]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    assert gpu.status() == tim.ERR_BAD_TREE and gpu.state()["seq_len"][0] == 100
+    # sequence ids must ascend
+    st = gpu.state()
+    ids = torch.tensor([1, 0], dtype=torch.int32, device="cuda")
+    gpu.ctx.tim_prune_plan(ids, 0, gpu.plan)
+    gpu.ctx.tim_kv_compact(gpu.plan, 0, 1)
+    gpu.ctx.tim_plan_commit(gpu.plan)
+    assert gpu.status() == tim.ERR_INVALID_ARG
+    assert np.array_equal(gpu.state()["seq_len"], st["seq_len"])
+    # host-side argument checks return at once
+    with pytest.raises(tim.TimError):
+        gpu.ctx.tim_kv_compact(gpu.plan, 0, 2)                 # layer_end beyond the context's layers
+    with pytest.raises(tim.TimError):
+        gpu.ctx.tim_prune_plan(ids, -1, gpu.plan)
