@@ -576,3 +576,36 @@ def test_malformed_tree_and_bad_sequence_list_are_rejected_without_damage(gb):
         gpu.ctx.tim_kv_compact(gpu.plan, 0, 2)                 # layer_end beyond the context's layers
     with pytest.raises(tim.TimError):
         gpu.ctx.tim_prune_plan(ids, -1, gpu.plan)
+
+
+@pytest.mark.parametrize("page_size", [16, 1])
+def test_stale_rows_holding_nan_or_inf_do_not_leak(gb, page_size):
+    """Rows past a sequence's end (and every free page) hold NaN / Inf bit patterns; attention,
+    the fused append, the masked variant, compaction and the extend attention must ignore them."""
+    seeds, p0s, steps = [91, 92, 93], [5, 33, 250], 40
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(7, steps, 3))
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=30 * (16 // page_size),
+                              page_size=page_size)
+    ora = OracleRuntime(cfg, 1)
+    harness.preload_oracle(ora, wl, 12, 1.0)
+    gpu = gb.GpuRuntime(cfg, 1)
+    poison = torch.tensor([0x7FC0, 0x7F80, 0xFF80, 0x7FFF], dtype=torch.int32).to(torch.int16)
+    for pool in (gpu.ctx.k_pool, gpu.ctx.v_pool):
+        flat = pool.view(torch.int16).view(-1)
+        flat.copy_(poison.to(flat.device).repeat(flat.numel() // 4 + 1)[: flat.numel()])
+    gb.preload_gpu(gpu, wl, 12, 1.0)
+    gpu.fused_append = True
+    for step in range(steps):
+        views = []
+        want = harness.run_step(ora, wl, step, 12, 1.0, 128 ** -0.5)
+        got = harness.run_step(gpu, wl, step, 12, 1.0, 128 ** -0.5, on_event=lambda s_, ev: views.append(gpu.plan_view()))
+        assert np.all(np.isfinite(got[0]))
+        check_attention(got[0], want[0])
+        q, _, _ = harness.step_inputs(12, step, cfg, 1.0)
+        masked = gpu.decode_attn_masked(0, q[0], 128 ** -0.5)           # mask is all-visible here: same result
+        assert np.all(np.isfinite(masked))
+        check_attention(masked, want[0])
+    check_state(ora, gpu)
+    check_kv(ora, gpu, drift_ok=True)
+    assert gpu.status() == 0
