@@ -299,7 +299,8 @@ int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan, const voi
                     int32_t n_ext_total, float sm_scale, int32_t out_dtype, tim_stream stream);
 
 /*
- * In-forward variant (Sec. 3.1 mentions it and rejects it as slower; Sec. 4.3's "80 % line"):
+ * In-forward variant (Sec. 3.1 mentions it and rejects it as slower; Sec. 4.3 plots it as a
+ * reference level below the baseline):
  * instead of moving anything, the tokens of the evicted lists are made invisible in
  * tim_state.keep_mask and tim_decode_attn_masked skips them inside attention: pages with no
  * visible token are not read, others are read in full and masked.  Positions, lengths,

@@ -8,11 +8,11 @@ and the start of its task's conclusion; the task's own thought and conclusion
 stay, as do the prompt and all tasks at the same or a higher level.
 
 Readings taken here (the paper is silent or uses two words):
-  * the buffer is first-in first-out: the paper calls it a stack but pops
-    "the earliest" list, and the Fig. 3 caption agrees;
+  * the buffer is first-in first-out: the paper names it a stack, yet the list it
+    removes is the one that entered first, and the Fig. 3 caption agrees;
   * eviction may be deferred: lists that left the buffer wait in `pending`
-    until the runtime flushes them before a decode step (Sec. 3.1 prunes
-    "before decoding").
+    until the runtime flushes them before a decode step (Sec. 3.1 places
+    pruning ahead of the decode step).
 """
 from collections import deque
 

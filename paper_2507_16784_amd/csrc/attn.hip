@@ -101,6 +101,13 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
   }
 }
 
+// A sequence with no tokens has no block that computes; slot 0 defines its output as zero.
+template <bool OUT_BF16>
+__device__ __forceinline__ void at_empty_out(const tim_config &cfg, void *out, int b, int kvh) {
+  for (int idx = threadIdx.x; idx < TIM_G * TIM_D; idx += AT_THREADS)
+    at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + kvh * TIM_G) * TIM_D + idx, 0.f);
+}
+
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
@@ -118,7 +125,10 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
   // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
   const int used = min(slots, (nchunks + cpb - 1) / cpb);
-  if (slot >= used) return;  // uniform for the block
+  if (slot >= used) {  // uniform for the block
+    if (n <= 0 && slot == 0) at_empty_out<OUT_BF16>(cfg, out, b, kvh);
+    return;
+  }
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
 
   // the group's four query rows, dims 8c..8c+7, pre-scaled so that exp2 gives softmax
@@ -272,7 +282,10 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
   // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
   const int used = min(slots, (nchunks + cpb - 1) / cpb);
-  if (slot >= used) return;  // uniform for the block
+  if (slot >= used) {  // uniform for the block
+    if (n <= 0 && slot == 0) at_empty_out<OUT_BF16>(cfg, out, b, kvh);
+    return;
+  }
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
 
   // B operand of the score product: Q^T, head j (zero for j >= 4), dims 32s + 8g .. +8

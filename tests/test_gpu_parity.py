@@ -609,3 +609,32 @@ def test_stale_rows_holding_nan_or_inf_do_not_leak(gb, page_size):
     check_state(ora, gpu)
     check_kv(ora, gpu, drift_ok=True)
     assert gpu.status() == 0
+
+
+def test_empty_sequences(gb):
+    """Degenerate inputs: attention over an empty working memory is defined as zero, a flush of
+    an empty sequence is a no-op, and a batch mixing empty and one-token sequences works."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    tr = Trace(64, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr, tr], [0, 1, 0], 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=8)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 1, 1.0)
+    gb.preload_gpu(gpu, wl, 1, 1.0)
+    q, k, v = harness.step_inputs(1, 0, cfg, 1.0)
+    got = gpu.decode_attn(0, q[0], 0.3)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0)
+    kb, vb = ora.gather_kv(0, 1)
+    from oracle import bf16 as obf
+    assert np.allclose(got[1], np.repeat(obf.to_f64(vb[0]), 4, axis=0), atol=1e-6)       # one token: its value
+    ev = ora.prune_plan([0, 1, 2]); ora.kv_compact(ev, 0, 1); ora.commit(ev)
+    pl = gpu.prune_plan([0, 1, 2]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    check_plan(ev, gpu.plan_view())
+    check_state(ora, gpu)
+    want = harness.run_step(ora, wl, 0, 1, 1.0, 0.3)
+    gpu.fused_append = True
+    got = harness.run_step(gpu, wl, 0, 1, 1.0, 0.3)
+    check_attention(got[0], want[0])
+    check_state(ora, gpu)
+    assert gpu.status() == 0
