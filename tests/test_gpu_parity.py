@@ -364,8 +364,9 @@ def test_extend_attention_after_flush(gb, case):
         assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("page_size", [16, 1])
 @pytest.mark.parametrize("threshold,cadence,spec_name", [(0, 4, "tiny"), (2, 9, "tiny"), (1, 16, "c1")])
-def test_in_forward_masked_variant(gb, threshold, cadence, spec_name):
+def test_in_forward_masked_variant(gb, threshold, cadence, spec_name, page_size):
     """The no-compaction variant: evicted lists only become invisible.  The visibility mask is
     compared bit for bit, attention over the visible tokens within the attention bars, and
     lengths / page tables / node coordinates must not move at all."""
@@ -376,7 +377,8 @@ def test_in_forward_masked_variant(gb, threshold, cadence, spec_name):
     traces = [generate(s, p + steps + 1, spec) for s, p in zip(seeds, p0s)]
     nseq = len(seeds)
     wl = Workload(traces, p0s, steps, every(cadence, steps, nseq))
-    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=12)
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=24 * (16 // page_size),
+                              page_size=page_size)
     ora = OracleRuntime(cfg, threshold)
     harness.preload_oracle(ora, wl, 4, 1.0)
     gpu = gb.GpuRuntime(cfg, threshold)
@@ -638,3 +640,49 @@ def test_empty_sequences(gb):
     check_attention(got[0], want[0])
     check_state(ora, gpu)
     assert gpu.status() == 0
+
+
+@pytest.mark.parametrize("page_size", [16, 1])
+def test_prune_from_the_first_token_and_prune_everything(gb, page_size):
+    """Degenerate plans: the pruned span starts at token 0 (no page can stay), and a list that
+    covers the whole sequence (nothing survives); decoding then continues from what is left."""
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    tr = Trace(400, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr], [90, 70], 20, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=10 * (16 // page_size), max_nodes=4,
+                              page_size=page_size)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 3, 1.0)
+    gb.preload_gpu(gpu, wl, 3, 1.0)
+    ops = [(0, MARK_OPEN, 0, 0), (0, MARK_SUB_BEGIN, 0, 0), (0, MARK_SUB_END, 0, 37),       # tokens 0..36 go
+           (1, MARK_OPEN, 0, 0), (1, MARK_SUB_BEGIN, 0, 0), (1, MARK_SUB_END, 0, 70)]       # all 70 tokens go
+    ora.mark(ops); gpu.mark(ops)
+    before = {(0, b): gpu.gather_kv(0, b) for b in (0, 1)}
+    ev = ora.prune_plan([0, 1]); ora.kv_compact(ev, 0, 1); ora.commit(ev)
+    pl = gpu.prune_plan([0, 1]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    check_plan(ev, gpu.plan_view())
+    check_event_kv(ora, gpu, ev, before)
+    check_state(ora, gpu)
+    assert list(ora.seq_len) == [53, 0]
+    gpu.fused_append = True
+    for step in range(20):
+        want = harness.run_step(ora, wl, step, 3, 1.0, 128 ** -0.5)
+        got = harness.run_step(gpu, wl, step, 3, 1.0, 128 ** -0.5)
+        check_attention(got[0], want[0])
+    check_state(ora, gpu)
+    assert gpu.status() == 0
+
+
+def test_softmax_scale_zero_and_negative(gb):
+    from paper_2507_16784_amd.workload.tree import Trace
+    tr = Trace(700, [], [], [], [], [], [], [])
+    wl = Workload([tr], [600], 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=4)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 4, 1.0)
+    gb.preload_gpu(gpu, wl, 4, 1.0)
+    q, _, _ = harness.step_inputs(4, 0, cfg, 1.0)
+    for scale in (0.0, -0.05, 0.5):
+        check_attention(gpu.decode_attn(0, q[0], scale), ora.decode_attn(0, q[0], scale))
