@@ -686,3 +686,66 @@ def test_softmax_scale_zero_and_negative(gb):
     q, _, _ = harness.step_inputs(4, 0, cfg, 1.0)
     for scale in (0.0, -0.05, 0.5):
         check_attention(gpu.decode_attn(0, q[0], scale), ora.decode_attn(0, q[0], scale))
+
+
+def test_decode_step_captured_in_a_hip_graph(gb):
+    """The decode calls launch kernels only (no allocation, no host sync, no memset), so a caller
+    can capture a step in a HIP graph.  The graph is replayed several times with eager work
+    and synchronisations in between, and every replay is checked against the oracle."""
+    from paper_2507_16784_amd.workload import tensors
+    seeds, p0s, steps = [95, 96], [40, 300], 12
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, {})
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=8)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 5, 1.0)
+    gb.preload_gpu(gpu, wl, 5, 1.0)
+    ctx = gpu.ctx
+    q = [tensors.normal_bf16(6, (l,), (2, 8, 128), 1.0).cuda() for l in range(2)]
+    kn = [tensors.normal_bf16(7, (l,), (2, 2, 128), 1.0).cuda() for l in range(2)]
+    vn = [tensors.normal_bf16(8, (l,), (2, 2, 128), 1.0).cuda() for l in range(2)]
+    outs = [torch.zeros(2, 8, 128, dtype=torch.float32, device="cuda") for _ in range(2)]
+
+    def step_calls():
+        ctx.tim_seq_advance()
+        for l in range(2):
+            ctx.tim_decode_attn_append(l, q[l], kn[l], vn[l], outs[l], 128 ** -0.5, 512)
+
+    def oracle_step():
+        ora.advance()
+        res = []
+        for l in range(2):
+            ora.append(l, tensors.bits(kn[l].cpu()), tensors.bits(vn[l].cpu()))
+            res.append(ora.decode_attn(l, tensors.bits(q[l].cpu()), 128 ** -0.5))
+        return res
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # one eager step on the side stream first
+        step_calls()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for a, b in zip(outs, oracle_step()):
+        check_attention(a.cpu().numpy(), b)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step_calls()
+    torch.cuda.synchronize()
+    check_state(ora, gpu)                               # capturing runs nothing
+    for i in range(5):
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle_step()
+        for a, b in zip(outs, want):
+            check_attention(a.cpu().numpy(), b)
+        check_state(ora, gpu)
+        # eager work between replays: a structure mark and an ordinary step
+        ops = [(0, 1, i % cfg.max_nodes, -1)]
+        ora.mark(ops); gpu.mark(ops)
+        step_calls()
+        torch.cuda.synchronize()
+        for a, b in zip(outs, oracle_step()):
+            check_attention(a.cpu().numpy(), b)
+    check_kv(ora, gpu)
+    assert gpu.status() == 0
