@@ -5,8 +5,10 @@ Integer state (plans, page tables, free stack, lengths, node coordinates) is com
 full against an oracle replay that carries no K/V (layers = 0).  Floating point is checked
 on sampled (layer, sequence) pairs the oracle can compute one by one: decode attention over
 sequences before and after their big flush, and the compaction of sampled layers of a
-flushed sequence judged on the GPU's own pre-flush rows.  The pool is filled by the seeded
-GPU generator, so sampled inputs are read back from the device.
+flushed sequence.  The pool is filled by the seeded GPU generator, so sampled inputs (rows no
+kernel has rewritten, and appended rows verified to be bit copies) are read back from the
+device; for a flushed sequence the oracle attends over its own re-rotation of those inputs,
+never over keys the HIP path produced.
 """
 import gc
 
@@ -74,6 +76,7 @@ def test_config3_full_size_sampled():
     out = torch.empty(64, 32, 128, dtype=torch.float32, device="cuda")
     sample_layers = [0, 17, 35]
     big = {0: 0, 4: 1, 8: 2}                                   # step -> sequence taking its big flush
+    okv = {}                                                   # (layer, flushed sequence) -> oracle-side [K, V] bits
     for step in range(STEPS):
         print(f"full-size step {step}", flush=True)
         ops = wl.step_ops(step)
@@ -105,17 +108,28 @@ def test_config3_full_size_sampled():
                     want[still] = kb[pl.kept_idx[still]]
                     n_tot, n_same = check_rotated(kg, want)
                     assert n_same >= 0.99 * n_tot
+                    okv[(l, big[step])] = [want, vb[pl.kept_idx]]
         ora.advance()
         ctx.tim_seq_advance()
         same_state()
         hint = int(ora.seq_len.max())
-        for layer in ([0, 17, 35] if step in (0, 5, 9) else [step % 36]):
+        for layer in sample_layers:
             q, kn, vn = rnd(64, 32, 128), rnd(64, 8, 128), rnd(64, 8, 128)
             ctx.tim_decode_attn_append(layer, q, kn, vn, out, shape.q_scale, hint)     # as bench.py launches it
             got = out.cpu().numpy()
-            for b in {0, 1, 2, 63, 31} if step in (0, 5, 9) else {big.get(step, 40)}:
+            kn_b, vn_b = tensors.bits(kn.cpu()), tensors.bits(vn.cpu())
+            for (l, b), kv in okv.items():                                             # the oracle's caches grow too
+                if l == layer:
+                    kv[0] = np.concatenate([kv[0], kn_b[b][None]])
+                    kv[1] = np.concatenate([kv[1], vn_b[b][None]])
+            for b in ({0, 1, 2, 63, 31} if step in (0, 4, 8, 9) else {big.get(step, 40)}):
                 kb, vb = _gather(ctx, layer, b)
-                assert np.array_equal(kb[-1], tensors.bits(kn[b].cpu()))        # the appended row is in place
+                assert np.array_equal(kb[-1], kn_b[b]) and np.array_equal(vb[-1], vn_b[b])   # appended rows: bit copies
+                if (layer, b) in okv:                      # flushed: attend over the oracle's own re-rotated keys
+                    ko, vo = okv[(layer, b)]
+                    assert np.array_equal(vb, vo)
+                    check_rotated(kb, ko)
+                    kb, vb = ko, vo
                 want = attend(bf16.to_f64(tensors.bits(q[b].cpu())), bf16.to_f64(kb), bf16.to_f64(vb), shape.q_scale)
                 check_attention(got[b], want.astype(np.float32))
         assert ctx.tim_status() == 0
