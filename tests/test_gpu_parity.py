@@ -95,7 +95,9 @@ def check_rotated(kg, ko):
 
 def check_event_kv(ora, gpu, ev, before):
     """One flush, judged on the GPU's own pre-flush cache: values and unmoved keys are bit
-    copies of the survivors, moved keys equal the oracle's rotation of the same stored bits."""
+    copies of the survivors, moved keys equal the oracle's rotation of the same stored bits.
+    This isolates one flush from rounding differences inherited from earlier ones; the cache
+    is also compared with the oracle's own, independent lineage (check_kv) after every flush."""
     c = ora.cfg
     tot = same = 0
     for sp in ev.seqs:
@@ -114,7 +116,7 @@ def check_event_kv(ora, gpu, ev, before):
     assert same >= 0.99 * tot
 
 
-def check_kv(ora, gpu, drift_ok=False):
+def check_kv(ora, gpu, drift_ok=False, oracle_is_ahead=False):
     """Whole working memory of every (layer, sequence), read through the page tables.  After
     several flushes the two caches may have rounded a key differently once and then rotated
     it again, so `drift_ok` only bounds that drift; a single flush is held to check_rotated."""
@@ -124,6 +126,8 @@ def check_kv(ora, gpu, drift_ok=False):
         for b in range(c.max_batch):
             ko, vo = ora.gather_kv(layer, b)
             kg, vg = gpu.gather_kv(layer, b)
+            if oracle_is_ahead:                                          # the oracle already appended this step's token
+                ko, vo = ko[: kg.shape[0]], vo[: vg.shape[0]]
             assert np.array_equal(vg, vo)                               # values: bit copies
             if drift_ok:
                 fo, fg = bf16.to_f64(ko), bf16.to_f64(kg)
@@ -166,6 +170,7 @@ def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_
             views.append(gpu.plan_view())
             if check_now:                       # right after the commit, before the next token lands
                 check_event_kv(ora, gpu, events[len(views) - 1], before)
+                check_kv(ora, gpu, drift_ok=n_events > 0, oracle_is_ahead=True)   # and the oracle's own lineage
 
         got = harness.run_step(gpu, wl, step, seed, kv_scale, sm_scale, attend=do_att, before_event=snapshot,
                                on_event=after_commit)
