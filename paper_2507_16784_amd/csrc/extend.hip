@@ -14,12 +14,14 @@
 // the CU's vector L1 serves three of the four reads.  Causality is a mask on the pages at
 // the diagonal only.  One lazy reference maximum per query row, as in decode.
 #include "tim_internal.h"
+#include <type_traits>
 
 #define EX_THREADS 256
 #define EX_TILE_TOKENS 32
 #define EX_WAVE_TOKENS 8
 #define EX_NEG_BIG (-1.0e30f)
 #define EX_LAZY_MAX 8.0f
+#define EX_LAZY_LIMIT 256.0f  // 2^EX_LAZY_MAX
 
 typedef __bf16 ex_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 ex_bf16x2 __attribute__((ext_vector_type(2)));
@@ -221,29 +223,60 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 
 // ---- LDS-staged variant ----------------------------------------------------------------
 // The four waves of a block need the same K and V tiles.  Instead of each wave pulling them
-// through the vector L1, each wave fetches one of the pair's four 4 KiB tiles (K page A, K page
-// B, V page A, V page B) with fully coalesced loads and parks it in LDS; all waves then read
-// their MFMA operands from LDS.  Two LDS buffers: the global loads of the next pair are in
-// flight while this pair is multiplied, and one barrier per pair separates readers from the
-// next writer.
+// through the vector L1, each wave copies one of the pair's four 4 KiB tiles (K page A, K page
+// B, V page A, V page B) from global memory straight into LDS, and all waves read their MFMA
+// operands from there.  Two LDS buffers: the copies of the next pair are in flight while this
+// pair is multiplied, and one barrier per pair separates readers from the next writer.
+//
+// Operands.  K (A operand of the score product) is read as "row n, 16-byte chunk 4 s + g".
+// V (B operand of the output product) is read with the transposing LDS load: lanes (g, j)
+// point at row 4 g + j / 4, dims 16 mf + 4 (j % 4) .. +3, and lane (g, n) receives
+// V[4 g + e][16 mf + n], e = 0..3, which together with the same read of the second page is
+// the B operand for output columns 16 mf .. 16 mf + 15.  No transposition in registers.
 //
 // Bank conflicts.  Measured on this chip: a 16-byte-per-lane LDS read is served 16 lanes at a
 // time, and the lanes served together are not consecutive: of lanes 0..31 they are
 // {0-3, 12-15, 20-23, 24-27} and {4-7, 8-11, 16-19, 28-31} (same for 32..63); such a group is
-// conflict-free when its 16-byte slots differ modulo 256 bytes.  A V tile is read as "row
-// 4g+i, chunk n": plain 256-byte rows already give every lane of a group its own slot.  A K
-// tile is read as "row n, chunk 4s+g": chunk c of row r is stored at slot c ^ r, which makes
-// the slots of each group a permutation of 0..15.  (Rows padded to 272 bytes, the usual
-// remedy, collide two-way under this grouping: measured 1.7 times slower.)
+// conflict-free when its 16-byte slots differ modulo 256 bytes.  For K, chunk c of row r is
+// stored at slot c ^ r, which makes the slots of each group a permutation of 0..15.  (Rows
+// padded to 272 bytes, the usual remedy, collide two-way under this grouping.)  For V, the
+// 32-byte unit u of row r is stored at unit u ^ (r % 8): the eight rows that a transposing
+// read touches per half-wave then lie in eight different 32-byte bank groups (measured
+// conflict-free; unswizzled the same read is 3.5 times slower).  The copy into LDS writes
+// 1 KiB (4 rows) per instruction in lane order, so the swizzle is applied on the global
+// side: each lane fetches the chunk that belongs in its slot.
+//
+// The copies are issued from inline assembly: the compiler, seeing its own builtin for the
+// same instruction, makes every LDS read of the kernel wait for all copies in flight (it
+// cannot tell the two buffers apart), which would serialise copy and compute.  The wait for
+// the copies is therefore written by hand before each barrier.
 #define EXL_TILE_BYTES TIM_TILE_BYTES
 #define EXL_BUF_BYTES (4 * EXL_TILE_BYTES)
 
+typedef __attribute__((address_space(3))) unsigned char *exl_lds_ptr;
+typedef short exl_s16x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base is wave-uniform)
+__device__ __forceinline__ void exl_copy16(const void *src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+}
+__device__ __forceinline__ void exl_wait_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+typedef unsigned int exl_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 exl_read16(exl_lds_ptr p) {
+  return __builtin_bit_cast(uint4, *(const __attribute__((address_space(3))) exl_u32x4 *)p);
+}
+// transposing read: see the operand note above
+__device__ __forceinline__ uint2 exl_read_tr(exl_lds_ptr p) {
+  return __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) exl_s16x4 *)p));
+}
+
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(EX_THREADS, 2)
 tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer,
                            const uint4 *__restrict__ q_ext, void *__restrict__ out_ext, int n_ext_total,
                            float scale_log2) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * EXL_BUF_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * EXL_BUF_BYTES];
   const int kvh = blockIdx.x;
   if (!pl.totals[TIM_TOT_OK] || (int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
   const int tile = pl.totals[TIM_TOT_EXT_TILES] - 1 - blockIdx.y;
@@ -253,14 +286,18 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
     if (pl.hdr[(int64_t)mid * TIM_PLAN_HDR + TIM_HDR_EXT_TILE_OFF] <= tile) lo = mid; else hi = mid - 1;
   }
   const int32_t *hdr = pl.hdr + (int64_t)lo * TIM_PLAN_HDR;
-  if (hdr[TIM_HDR_BAD]) return;  // uniform for the block
+  if (hdr[TIM_HDR_BAD]) return;  // uniform for the block, like every exit before the barriers
   const int b = hdr[TIM_HDR_SEQ], m = hdr[TIM_HDR_N_KEPT], f = hdr[TIM_HDR_FIRST_PRUNED];
   const int ext = hdr[TIM_HDR_EXT], ext_off = hdr[TIM_HDR_EXT_OFF];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, n = lane & 15;
   const int blk_tok0 = (tile - hdr[TIM_HDR_EXT_TILE_OFF]) * EX_TILE_TOKENS;
   const int tok0 = blk_tok0 + w * EX_WAVE_TOKENS;
-  const bool active = tok0 < ext;  // a wave without a token still fetches and meets the barriers
+  const bool active = tok0 < ext;  // a wave without a token still copies and meets the barriers
 
+  // B operands of the score product: column n of set s is (token 4 s + n / 4, head n % 4).
+  // A negative scale is applied as |scale| to -q, which is exact.
+  const uint32_t q_flip = scale_log2 < 0.f ? 0x80008000u : 0u;
+  const float scale_abs = fabsf(scale_log2);
   uint4 qb[2][4];
   int pos[2];
 #pragma unroll
@@ -270,15 +307,24 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
     pos[s] = ok ? f + tl : -1;
 #pragma unroll
     for (int step = 0; step < 4; ++step) {
-      qb[s][step] = make_uint4(0, 0, 0, 0);
-      if (ok) qb[s][step] = q_ext[((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + (n & 3)) * 16 + 4 * step + g];
+      uint4 q = make_uint4(0, 0, 0, 0);
+      if (ok) q = q_ext[((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + (n & 3)) * 16 + 4 * step + g];
+      qb[s][step] = make_uint4(q.x ^ q_flip, q.y ^ q_flip, q.z ^ q_flip, q.w ^ q_flip);
     }
   }
-  const int first_pos = f + tok0;
-  const int last_pos = f + min(tok0 + EX_WAVE_TOKENS, ext) - 1;            // this wave's largest position
-  const int last_page = (f + min(blk_tok0 + EX_TILE_TOKENS, ext) - 1) / TIM_PS;  // the block's last key page
+  const int blk_first_pos = f + blk_tok0;
+  const int last_pos = f + min(tok0 + EX_WAVE_TOKENS, ext) - 1;  // this wave's largest position
+  // block-uniform: the pairs of pages the block walks, and how many of them lie wholly at or
+  // before its first position (no mask, no stale row, both pages present)
+  const int last_page = (f + min(blk_tok0 + EX_TILE_TOKENS, ext) - 1) / TIM_PS;
+  const int n_pairs = last_page / 2 + 1;
+  const int n_full = min(n_pairs, (blk_first_pos + 1) / (2 * TIM_PS));
 
-  float m_ref[2] = {EX_NEG_BIG, EX_NEG_BIG}, l_part[2] = {0.f, 0.f};
+  // The softmax denominators come from the matrix cores too: P times a column of ones, in the
+  // same layout (row 4 g + r in register r) as the output accumulators.
+  const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+  float m_ref[2] = {EX_NEG_BIG, EX_NEG_BIG};
+  ex_f32x4 lsum[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
   ex_f32x4 acc[2][8];
 #pragma unroll
   for (int s = 0; s < 2; ++s)
@@ -290,167 +336,182 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
-  // this wave's share of a pair: tile w (0: K page A, 1: K page B, 2: V page A, 3: V page B)
+  // ---- the copy side: this wave's tile of a pair is tile w
   const uint4 *tile_pool = w < 2 ? kpool : vpool;
-  // 16-byte unit i * 64 + lane of the tile is chunk lane % 16 of row 4 i + lane / 16
-  const int park_row = lane >> 4, park_chunk = lane & 15, park_swz = w < 2 ? 15 : 0;
-  unsigned char *park_base = lds + w * EXL_TILE_BYTES + park_row * 256;
-  uint4 stage0, stage1, stage2, stage3;
-  // The page id of a tile is read one pair before the tile itself, so that its latency is not in the way.
-#define EXL_PAGE_ID(pg_) ptab[min((pg_) + (w & 1), last_page)]
-#define EXL_FETCH(pid_)                                                                                         \
-  {                                                                                                             \
-    int phys_ = __builtin_amdgcn_readfirstlane(pid_);                                                           \
-    if (phys_ < 0 || phys_ >= cfg.num_pages) {                                                                  \
-      tim_set_status(st.status, TIM_ERR_INVALID_ARG); /* never dereference a bad page id */                     \
-      phys_ = 0;                                                                                                \
-    }                                                                                                           \
-    const uint4 *src_ = tile_pool + ((layer_base + phys_) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16) + lane; \
-    stage0 = src_[0];                                                                                           \
-    stage1 = src_[64];                                                                                          \
-    stage2 = src_[128];                                                                                         \
-    stage3 = src_[192];                                                                                         \
+  int src_unit[4];  // which 16-byte unit of the tile lane l fetches with copy i (slot l % 16 of row 4 i + l / 16)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * i + (lane >> 4), slot = lane & 15;
+    src_unit[i] = r * 16 + (w < 2 ? slot ^ r : slot ^ ((r & 7) << 1));
   }
-#define EXL_PARK(buf_)                                                                  \
-  {                                                                                     \
-    unsigned char *dst_ = park_base + (buf_) * EXL_BUF_BYTES;                           \
-    *reinterpret_cast<uint4 *>(dst_ + ((park_chunk ^ (park_row & park_swz)) << 4)) = stage0;                \
-    *reinterpret_cast<uint4 *>(dst_ + 4 * 256 + ((park_chunk ^ ((park_row + 4) & park_swz)) << 4)) = stage1;  \
-    *reinterpret_cast<uint4 *>(dst_ + 8 * 256 + ((park_chunk ^ ((park_row + 8) & park_swz)) << 4)) = stage2;  \
-    *reinterpret_cast<uint4 *>(dst_ + 12 * 256 + ((park_chunk ^ ((park_row + 12) & park_swz)) << 4)) = stage3; \
+  const uint32_t lds_base = (uint32_t)(size_t)lds;
+  const uint32_t copy_base = __builtin_amdgcn_readfirstlane(lds_base + w * EXL_TILE_BYTES);
+  // The page id of a tile is read one pair before the tile itself, so that its latency is not in the way.
+  auto page_id = [&](int pair_) { return ptab[min(2 * pair_ + (w & 1), last_page)]; };
+  int pid_next = page_id(0);
+  auto copy_tile = [&](int pid, int buf) {
+    int phys = __builtin_amdgcn_readfirstlane(pid);
+    if (phys < 0 || phys >= cfg.num_pages) {
+      tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
+      phys = 0;
+    }
+    const uint4 *src = tile_pool + ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+    const uint32_t dst = copy_base + buf * EXL_BUF_BYTES;
+    exl_copy16(src + src_unit[0], dst);
+    exl_copy16(src + src_unit[1], dst + 1024);
+    exl_copy16(src + src_unit[2], dst + 2048);
+    exl_copy16(src + src_unit[3], dst + 3072);
+  };
+
+  // ---- the read side: LDS offsets of this lane's operands within a buffer
+  const exl_lds_ptr lds3 = (exl_lds_ptr)lds;
+  int k_off[4], v_off[8];
+#pragma unroll
+  for (int step = 0; step < 4; ++step) k_off[step] = n * 256 + (((4 * step + g) ^ n) << 4);
+  {
+    const int r = 4 * g + (n >> 2);
+#pragma unroll
+    for (int mf = 0; mf < 8; ++mf) v_off[mf] = 2 * EXL_TILE_BYTES + r * 256 + ((mf ^ (r & 7)) << 5) + 8 * (n & 3);
   }
 
-  int pid_next = EXL_PAGE_ID(0);
-  EXL_FETCH(pid_next);
-  pid_next = EXL_PAGE_ID(2);
-  EXL_PARK(0);
-  __syncthreads();
-  for (int pg = 0, it = 0; pg <= last_page; pg += 2, ++it) {
-    const bool more = pg + 2 <= last_page;
-    if (more) {
-      EXL_FETCH(pid_next);
-      pid_next = EXL_PAGE_ID(pg + 4);
+  // One pair of pages, in LDS buffer BUF, against this wave's 32 query rows.  DIAG: the pair may hold
+  // keys beyond some row's own position, rows past the sequence, or no second page (the DIAG instance is
+  // also correct for any other pair, only slower).
+  //
+  // Lazy reference maximum, checked on the weights: the weights are first computed against the current
+  // reference; only if one of them exceeds 2^EX_LAZY_MAX (or the reference was never set) is the
+  // reference renewed from the scores, the accumulators rescaled and the weights recomputed.
+  auto pair = [&](int pr_idx, auto diag_c, auto buf_c) {
+    constexpr bool DIAG = decltype(diag_c)::value;
+    constexpr int BUF = decltype(buf_c)::value;
+    const exl_lds_ptr buf = lds3 + BUF * EXL_BUF_BYTES;
+    const int pg = 2 * pr_idx;
+    const bool has_b = !DIAG || pg + 1 <= last_page;
+    const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
+    uint4 ka[4], kb[4];
+#pragma unroll
+    for (int step = 0; step < 4; ++step) {
+      ka[step] = exl_read16(buf + k_off[step]);
+      kb[step] = exl_read16(buf + EXL_TILE_BYTES + k_off[step]);
     }
-    if (active && pg * TIM_PS <= last_pos) {
-      const unsigned char *buf = lds + (it & 1) * EXL_BUF_BYTES;
-      const bool has_b = pg + 1 <= last_page;
-      uint4 ka[4], kb[4], va[4], vb[4];
+    uint4 pw[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      ex_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int step = 0; step < 4; ++step) {
-        ka[step] = *reinterpret_cast<const uint4 *>(buf + n * 256 + (((4 * step + g) ^ n) << 4));
-        kb[step] = *reinterpret_cast<const uint4 *>(buf + EXL_TILE_BYTES + n * 256 + (((4 * step + g) ^ n) << 4));
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(ka[step]), ex_as_bf16x8(qb[s][step]), sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(kb[step]), ex_as_bf16x8(qb[s][step]), sb, 0, 0, 0);
       }
+      float raw[8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        va[i] = *reinterpret_cast<const uint4 *>(buf + 2 * EXL_TILE_BYTES + (4 * g + i) * 256 + n * 16);
-        vb[i] = *reinterpret_cast<const uint4 *>(buf + 3 * EXL_TILE_BYTES + (4 * g + i) * 256 + n * 16);
+      for (int r = 0; r < 4; ++r) {
+        raw[r] = sa[r];
+        raw[4 + r] = sb[r];
       }
-      const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
-      const bool diag = !has_b || (pg + 2) * TIM_PS - 1 > first_pos;
-      if (diag) {
+      if (DIAG) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {  // rows past the sequence may hold anything
-          if (key_a + r >= m) va[r] = make_uint4(0, 0, 0, 0);
-          if (!has_b || key_b + r >= m) vb[r] = make_uint4(0, 0, 0, 0);
+        for (int r = 0; r < 4; ++r) {  // a masked score is a large negative finite number: it survives a zero scale
+          if (key_a + r > pos[s]) raw[r] = EX_NEG_BIG;
+          if (!has_b || key_b + r > pos[s]) raw[4 + r] = EX_NEG_BIG;
         }
       }
-      uint4 pw[2];
+      float pe[8];
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        ex_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+      for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[e], scale_abs, -m_ref[s]));
+      const float pmax = fmaxf(fmaxf(fmaxf(pe[0], pe[1]), fmaxf(pe[2], pe[3])), fmaxf(fmaxf(pe[4], pe[5]), fmaxf(pe[6], pe[7])));
+      if (__any(pmax > EX_LAZY_LIMIT)) {  // also taken on the first pair: every weight is then infinite
+        float x = scale_abs * fmaxf(fmaxf(fmaxf(raw[0], raw[1]), fmaxf(raw[2], raw[3])),
+                                    fmaxf(fmaxf(raw[4], raw[5]), fmaxf(raw[6], raw[7])));
+        x = fmaxf(x, __shfl_xor(x, 16, 64));
+        x = fmaxf(x, __shfl_xor(x, 32, 64));
+        const float m_new = fmaxf(m_ref[s], x);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref[s] - m_new);
+        m_ref[s] = m_new;
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
-          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(ka[step]), ex_as_bf16x8(qb[s][step]), sa, 0, 0, 0);
+        for (int r = 0; r < 4; ++r) {
+          const float ar = __shfl(alpha, 4 * g + r, 64);
+          lsum[s][r] *= ar;
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
-          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(kb[step]), ex_as_bf16x8(qb[s][step]), sb, 0, 0, 0);
-        float t[8];
-        if (!diag) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            t[r] = sa[r] * scale_log2;
-            t[4 + r] = sb[r] * scale_log2;
-          }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            t[r] = key_a + r <= pos[s] ? sa[r] * scale_log2 : -INFINITY;
-            t[4 + r] = (has_b && key_b + r <= pos[s]) ? sb[r] * scale_log2 : -INFINITY;
-          }
+          for (int mf = 0; mf < 8; ++mf) acc[s][mf][r] *= ar;
         }
-        const float lm = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
-        if (__any(lm > m_ref[s] + EX_LAZY_MAX)) {
-          float x = lm;
-          x = fmaxf(x, __shfl_xor(x, 16, 64));
-          x = fmaxf(x, __shfl_xor(x, 32, 64));
-          const float m_new = fmaxf(m_ref[s], x);
-          const float alpha = __builtin_amdgcn_exp2f(m_ref[s] - m_new);
-          l_part[s] *= alpha;
-          m_ref[s] = m_new;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float ar = __shfl(alpha, 4 * g + r, 64);
-#pragma unroll
-            for (int mf = 0; mf < 8; ++mf) acc[s][mf][r] *= ar;
-          }
-        }
-        float pr[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          pr[e] = __builtin_amdgcn_exp2f(t[e] - m_ref[s]);
-          l_part[s] += pr[e];
-        }
-        pw[s].x = ex_pack_bf16(pr[0], pr[1]);
-        pw[s].y = ex_pack_bf16(pr[2], pr[3]);
-        pw[s].z = ex_pack_bf16(pr[4], pr[5]);
-        pw[s].w = ex_pack_bf16(pr[6], pr[7]);
+        for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[e], scale_abs, -m_ref[s]));
       }
-      const uint32_t *ra[8] = {&va[0].x, &va[1].x, &va[2].x, &va[3].x, &vb[0].x, &vb[1].x, &vb[2].x, &vb[3].x};
+      if (DIAG) {
 #pragma unroll
-      for (int mf = 0; mf < 8; ++mf) {
-        uint4 col;
-        uint32_t *cw = &col.x;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t x0 = ra[2 * u][mf >> 1], x1 = ra[2 * u + 1][mf >> 1];
-          cw[u] = (mf & 1) ? __builtin_amdgcn_perm(x1, x0, 0x07060302u) : __builtin_amdgcn_perm(x1, x0, 0x05040100u);
+        for (int r = 0; r < 4; ++r) {
+          if (key_a + r > pos[s]) pe[r] = 0.f;
+          if (!has_b || key_b + r > pos[s]) pe[4 + r] = 0.f;
         }
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-          acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
       }
+      pw[s].x = ex_pack_bf16(pe[0], pe[1]);
+      pw[s].y = ex_pack_bf16(pe[2], pe[3]);
+      pw[s].z = ex_pack_bf16(pe[4], pe[5]);
+      pw[s].w = ex_pack_bf16(pe[6], pe[7]);
+      lsum[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(ones), lsum[s], 0, 0, 0);
     }
-    if (more) EXL_PARK((it + 1) & 1);
+    uint4 live = make_uint4(~0u, ~0u, ~0u, ~0u);  // rows past the sequence may hold anything: their V is cleared
+    if (DIAG) {
+      live.x = (key_a + 0 < m ? 0x0000FFFFu : 0u) | (key_a + 1 < m ? 0xFFFF0000u : 0u);
+      live.y = (key_a + 2 < m ? 0x0000FFFFu : 0u) | (key_a + 3 < m ? 0xFFFF0000u : 0u);
+      live.z = has_b ? (key_b + 0 < m ? 0x0000FFFFu : 0u) | (key_b + 1 < m ? 0xFFFF0000u : 0u) : 0u;
+      live.w = has_b ? (key_b + 2 < m ? 0x0000FFFFu : 0u) | (key_b + 3 < m ? 0xFFFF0000u : 0u) : 0u;
+    }
+#pragma unroll
+    for (int mf = 0; mf < 8; ++mf) {
+      const uint2 ta = exl_read_tr(buf + v_off[mf]), tb = exl_read_tr(buf + EXL_TILE_BYTES + v_off[mf]);
+      uint4 col = make_uint4(ta.x, ta.y, tb.x, tb.y);
+      if (DIAG) col = make_uint4(col.x & live.x, col.y & live.y, col.z & live.z, col.w & live.w);
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
+    }
+  };
+  // Pair p is multiplied out of buffer p % 2 while pair p + 1 is copied into the other one, which every
+  // wave left at the barrier that ended pair p - 1.  All bounds are the same for the whole block.
+  auto step = [&](int p, auto diag_c, auto buf_c) {
+    constexpr int BUF = decltype(buf_c)::value;
+    if (p + 1 < n_pairs) {
+      copy_tile(pid_next, 1 - BUF);
+      pid_next = page_id(p + 2);
+    }
+    if (active && 2 * p * TIM_PS <= last_pos) pair(p, diag_c, buf_c);
+    exl_wait_copies();
     __syncthreads();
+  };
+  using exl_b0 = std::integral_constant<int, 0>;
+  using exl_b1 = std::integral_constant<int, 1>;
+
+  copy_tile(pid_next, 0);
+  pid_next = page_id(1);
+  exl_wait_copies();
+  __syncthreads();
+  int p = 0;
+  for (; p + 2 <= n_full; p += 2) {  // two pairs per trip, so that the buffer is known at compile time
+    step(p, std::false_type{}, exl_b0{});
+    step(p + 1, std::false_type{}, exl_b1{});
   }
-#undef EXL_PAGE_ID
-#undef EXL_FETCH
-#undef EXL_PARK
+  for (; p < n_pairs; ++p) {  // the last of the full pairs, if their number is odd, and the pairs at the diagonal
+    if (p & 1) step(p, std::true_type{}, exl_b1{});
+    else step(p, std::true_type{}, exl_b0{});
+  }
   if (!active) return;
 
+  // lane (g, n) holds, for row (token 4 s + g, head r), output columns 16 mf + n
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    float lt = l_part[s];
-    lt += __shfl_xor(lt, 16, 64);
-    lt += __shfl_xor(lt, 32, 64);
     const int tl = tok0 + 4 * s + g;
-    const bool ok = tl < ext && ext_off + tl < n_ext_total;
+    if (!(tl < ext && ext_off + tl < n_ext_total)) continue;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float inv = 1.f / __shfl(lt, 4 * g + r, 64);
-      if (!ok) continue;
-      const int64_t o = ((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + r) * TIM_D + 8 * n;
-      if (OUT_BF16) {
-        uint4 v;
-        v.x = ex_pack_bf16(acc[s][0][r] * inv, acc[s][1][r] * inv);
-        v.y = ex_pack_bf16(acc[s][2][r] * inv, acc[s][3][r] * inv);
-        v.z = ex_pack_bf16(acc[s][4][r] * inv, acc[s][5][r] * inv);
-        v.w = ex_pack_bf16(acc[s][6][r] * inv, acc[s][7][r] * inv);
-        *reinterpret_cast<uint4 *>(reinterpret_cast<__bf16 *>(out_ext) + o) = v;
-      } else {
-        float *dst = reinterpret_cast<float *>(out_ext) + o;
-        *reinterpret_cast<float4 *>(dst) = make_float4(acc[s][0][r] * inv, acc[s][1][r] * inv, acc[s][2][r] * inv, acc[s][3][r] * inv);
-        *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[s][4][r] * inv, acc[s][5][r] * inv, acc[s][6][r] * inv, acc[s][7][r] * inv);
+      const float inv = 1.f / lsum[s][r];
+      const int64_t o = ((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + r) * TIM_D + n;
+#pragma unroll
+      for (int mf = 0; mf < 8; ++mf) {
+        const float y = acc[s][mf][r] * inv;
+        if (OUT_BF16) reinterpret_cast<__bf16 *>(out_ext)[o + 16 * mf] = (__bf16)y;
+        else reinterpret_cast<float *>(out_ext)[o + 16 * mf] = y;
       }
     }
   }
@@ -470,7 +531,7 @@ extern "C" int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan
   dim3 grid(ctx->cfg.kv_heads, tiles);
   const float scale_log2 = sm_scale * 1.4426950408889634f;
   const uint4 *q4 = reinterpret_cast<const uint4 *>(q_ext);
-  if (ctx->extend_lds) {
+  if (ctx->extend_lds) {  // (the kernel's LDS array is the only one, so its offset in LDS is 0 and 1 KiB-aligned)
     if (out_dtype == TIM_OUT_BF16)
       hipLaunchKernelGGL((tim_extend_attn_lds_kernel<true>), grid, dim3(EX_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st,
                          *plan, plan->n_seqs, layer, q4, out_ext, n_ext_total, scale_log2);
