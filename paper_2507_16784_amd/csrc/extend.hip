@@ -251,7 +251,7 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 // cannot tell the two buffers apart), which would serialise copy and compute.  The wait for
 // the copies is therefore written by hand before each barrier.
 #define EXL_TILE_BYTES TIM_TILE_BYTES
-#define EXL_BUF_BYTES (4 * EXL_TILE_BYTES)
+#define EXL_PAIR_BYTES (2 * EXL_TILE_BYTES)  // one pair of pages of K, or of V
 
 typedef __attribute__((address_space(3))) unsigned char *exl_lds_ptr;
 typedef short exl_s16x4 __attribute__((ext_vector_type(4)));
@@ -276,7 +276,7 @@ __global__ void __launch_bounds__(EX_THREADS, 2)
 tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer,
                            const uint4 *__restrict__ q_ext, void *__restrict__ out_ext, int n_ext_total,
                            float scale_log2) {
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * EXL_BUF_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * EXL_PAIR_BYTES];
   const int kvh = blockIdx.x;
   if (!pl.totals[TIM_TOT_OK] || (int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
   const int tile = pl.totals[TIM_TOT_EXT_TILES] - 1 - blockIdx.y;
@@ -336,165 +336,197 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
-  // ---- the copy side: this wave's tile of a pair is tile w
-  const uint4 *tile_pool = w < 2 ? kpool : vpool;
+  // ---- LDS: K of pairs p + 1 and p + 2, V of pairs p and p + 1 (the scores run one pair ahead of
+  // the products): [K parity 0: page A, page B][K parity 1][V parity 0][V parity 1], 8 KiB each
+  // ---- the copy side: waves 0 and 1 bring K pages A and B, waves 2 and 3 bring V pages A and B
+  const int ws = __builtin_amdgcn_readfirstlane(w);
+  const bool k_wave = ws < 2;
+  const uint4 *tile_pool = k_wave ? kpool : vpool;
   int src_unit[4];  // which 16-byte unit of the tile lane l fetches with copy i (slot l % 16 of row 4 i + l / 16)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = 4 * i + (lane >> 4), slot = lane & 15;
-    src_unit[i] = r * 16 + (w < 2 ? slot ^ r : slot ^ ((r & 7) << 1));
+    src_unit[i] = r * 16 + (k_wave ? slot ^ r : slot ^ ((r & 7) << 1));
   }
-  const uint32_t lds_base = (uint32_t)(size_t)lds;
-  const uint32_t copy_base = __builtin_amdgcn_readfirstlane(lds_base + w * EXL_TILE_BYTES);
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
+  const uint32_t copy_base = lds_base + (k_wave ? 0 : 2 * EXL_PAIR_BYTES) + (ws & 1) * EXL_TILE_BYTES;
   // The page id of a tile is read one pair before the tile itself, so that its latency is not in the way.
-  auto page_id = [&](int pair_) { return ptab[min(2 * pair_ + (w & 1), last_page)]; };
-  int pid_next = page_id(0);
-  auto copy_tile = [&](int pid, int buf) {
+  auto page_id = [&](int pair_) { return ptab[min(2 * pair_ + (ws & 1), last_page)]; };
+  auto copy_tile = [&](int pid, int parity) {
     int phys = __builtin_amdgcn_readfirstlane(pid);
     if (phys < 0 || phys >= cfg.num_pages) {
       tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
       phys = 0;
     }
     const uint4 *src = tile_pool + ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-    const uint32_t dst = copy_base + buf * EXL_BUF_BYTES;
+    const uint32_t dst = copy_base + parity * EXL_PAIR_BYTES;
     exl_copy16(src + src_unit[0], dst);
     exl_copy16(src + src_unit[1], dst + 1024);
     exl_copy16(src + src_unit[2], dst + 2048);
     exl_copy16(src + src_unit[3], dst + 3072);
   };
 
-  // ---- the read side: LDS offsets of this lane's operands within a buffer
+  // ---- the read side: LDS offsets of this lane's operands within a pair's 8 KiB
   const exl_lds_ptr lds3 = (exl_lds_ptr)lds;
-  int k_off[4], v_off[8];
+  int k_off[4];
 #pragma unroll
   for (int step = 0; step < 4; ++step) k_off[step] = n * 256 + (((4 * step + g) ^ n) << 4);
-  {
-    const int r = 4 * g + (n >> 2);
-#pragma unroll
-    for (int mf = 0; mf < 8; ++mf) v_off[mf] = 2 * EXL_TILE_BYTES + r * 256 + ((mf ^ (r & 7)) << 5) + 8 * (n & 3);
-  }
+  // V: row r = 4 g + n / 4, unit mf ^ (r % 8), piece n % 4; the unit is three address bits of their own,
+  // so the offset for column block mf is v_off0 ^ (mf << 5)
+  const int v_off0 = 2 * EXL_PAIR_BYTES + (4 * g + (n >> 2)) * 256 + (((4 * g + (n >> 2)) & 7) << 5) + 8 * (n & 3);
 
-  // One pair of pages, in LDS buffer BUF, against this wave's 32 query rows.  DIAG: the pair may hold
-  // keys beyond some row's own position, rows past the sequence, or no second page (the DIAG instance is
-  // also correct for any other pair, only slower).
-  //
-  // Lazy reference maximum, checked on the weights: the weights are first computed against the current
-  // reference; only if one of them exceeds 2^EX_LAZY_MAX (or the reference was never set) is the
-  // reference renewed from the scores, the accumulators rescaled and the weights recomputed.
-  auto pair = [&](int pr_idx, auto diag_c, auto buf_c) {
-    constexpr bool DIAG = decltype(diag_c)::value;
-    constexpr int BUF = decltype(buf_c)::value;
-    const exl_lds_ptr buf = lds3 + BUF * EXL_BUF_BYTES;
-    const int pg = 2 * pr_idx;
-    const bool has_b = !DIAG || pg + 1 <= last_page;
-    const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
-    uint4 ka[4], kb[4];
+  // scores of the pair whose K lies in the K buffer of parity PAR: both row sets, raw (unscaled, unmasked)
+  auto scores = [&](auto par_c, float (&raw)[2][8]) {
+    const int PAR = par_c;  // a compile-time constant in the hot loop
+    const exl_lds_ptr buf = lds3 + PAR * EXL_PAIR_BYTES;
+    ex_f32x4 sa[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, sb[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int step = 0; step < 4; ++step) {
-      ka[step] = exl_read16(buf + k_off[step]);
-      kb[step] = exl_read16(buf + EXL_TILE_BYTES + k_off[step]);
-    }
-    uint4 pw[2];
+    for (int step = 0; step < 4; ++step) {  // four independent accumulation chains; K operands live one step only
+      // LDS reads may not be moved up across this point (everything else may): otherwise all eight K
+      // operands are fetched first and the kernel runs out of registers
+      if (step == 2) __builtin_amdgcn_sched_barrier(0x7F);
+      const uint4 ka = exl_read16(buf + k_off[step]), kb = exl_read16(buf + EXL_TILE_BYTES + k_off[step]);
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      ex_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int step = 0; step < 4; ++step) {
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(ka[step]), ex_as_bf16x8(qb[s][step]), sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(kb[step]), ex_as_bf16x8(qb[s][step]), sb, 0, 0, 0);
+      for (int s = 0; s < 2; ++s) {
+        sa[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(ka), ex_as_bf16x8(qb[s][step]), sa[s], 0, 0, 0);
+        sb[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(kb), ex_as_bf16x8(qb[s][step]), sb[s], 0, 0, 0);
       }
-      float raw[8];
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        raw[r] = sa[r];
-        raw[4 + r] = sb[r];
+        raw[s][r] = sa[s][r];
+        raw[s][4 + r] = sb[s][r];
       }
+  };
+
+  // One trip of the pipeline, pair p of parity PAR = p % 2: the scores of pair p + 1 go through the matrix
+  // cores while the vector units turn the scores of pair p (in `cur`) into weights; then the products of
+  // pair p.  Meanwhile K of pair p + 2 and V of pair p + 1 are copied in.  DIAG: pair p may hold keys
+  // beyond some row's own position, rows past the sequence, or no second page (the DIAG instance is also
+  // correct for any other pair, only slower).
+  //
+  // Lazy reference maximum, checked on the weights: they are first computed against the current
+  // reference; only if one of them exceeds 2^EX_LAZY_MAX (always on the first pair: every weight is then
+  // infinite) is the reference renewed from the scores, the accumulators rescaled and the weights redone.
+  int pid_next;
+  auto trip = [&](int p, auto diag_c, auto par_c, float (&cur)[2][8], float (&nxt)[2][8]) {
+    constexpr bool DIAG = decltype(diag_c)::value;
+    const int PAR = par_c;  // a compile-time constant in the hot loop
+    {
+      const int cp = p + (k_wave ? 2 : 1);  // K of pair p + 2 into K parity PAR, V of pair p + 1 into V parity 1 - PAR;
+      if (cp < n_pairs) copy_tile(pid_next, k_wave ? PAR : 1 - PAR);  // every wave left those at the last barrier
+      pid_next = page_id(cp + 1);
+    }
+    if (active) {
+      const int pg = 2 * p;
+      const bool has_b = !DIAG || pg + 1 <= last_page;
+      const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
+      scores(1 - PAR, nxt);  // past the last pair this reads stale tiles; unused
+      // weights of set s against the current reference, packed; returns their largest
+      auto weights = [&](int s, uint4 &packed) {
+        float pe[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[s][e], scale_abs, -m_ref[s]));
+        const float top = fmaxf(fmaxf(fmaxf(pe[0], pe[1]), fmaxf(pe[2], pe[3])), fmaxf(fmaxf(pe[4], pe[5]), fmaxf(pe[6], pe[7])));
+        if (DIAG) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (key_a + r > pos[s]) pe[r] = 0.f;
+            if (!has_b || key_b + r > pos[s]) pe[4 + r] = 0.f;
+          }
+        }
+        packed.x = ex_pack_bf16(pe[0], pe[1]);
+        packed.y = ex_pack_bf16(pe[2], pe[3]);
+        packed.z = ex_pack_bf16(pe[4], pe[5]);
+        packed.w = ex_pack_bf16(pe[6], pe[7]);
+        return top;
+      };
       if (DIAG) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {  // a masked score is a large negative finite number: it survives a zero scale
-          if (key_a + r > pos[s]) raw[r] = EX_NEG_BIG;
-          if (!has_b || key_b + r > pos[s]) raw[4 + r] = EX_NEG_BIG;
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {  // a masked score is a large negative finite number: it survives a zero scale
+            if (key_a + r > pos[s]) cur[s][r] = EX_NEG_BIG;
+            if (!has_b || key_b + r > pos[s]) cur[s][4 + r] = EX_NEG_BIG;
+          }
+      }
+      uint4 pw[2];
+      const float pmax = fmaxf(weights(0, pw[0]), weights(1, pw[1]));
+      if (__any(pmax > EX_LAZY_LIMIT)) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          float x = scale_abs * fmaxf(fmaxf(fmaxf(cur[s][0], cur[s][1]), fmaxf(cur[s][2], cur[s][3])),
+                                      fmaxf(fmaxf(cur[s][4], cur[s][5]), fmaxf(cur[s][6], cur[s][7])));
+          x = fmaxf(x, __shfl_xor(x, 16, 64));
+          x = fmaxf(x, __shfl_xor(x, 32, 64));
+          const float m_new = fmaxf(m_ref[s], x);
+          const float alpha = __builtin_amdgcn_exp2f(m_ref[s] - m_new);
+          m_ref[s] = m_new;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float ar = __shfl(alpha, 4 * g + r, 64);
+            lsum[s][r] *= ar;
+#pragma unroll
+            for (int mf = 0; mf < 8; ++mf) acc[s][mf][r] *= ar;
+          }
+          weights(s, pw[s]);
         }
       }
-      float pe[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[e], scale_abs, -m_ref[s]));
-      const float pmax = fmaxf(fmaxf(fmaxf(pe[0], pe[1]), fmaxf(pe[2], pe[3])), fmaxf(fmaxf(pe[4], pe[5]), fmaxf(pe[6], pe[7])));
-      if (__any(pmax > EX_LAZY_LIMIT)) {  // also taken on the first pair: every weight is then infinite
-        float x = scale_abs * fmaxf(fmaxf(fmaxf(raw[0], raw[1]), fmaxf(raw[2], raw[3])),
-                                    fmaxf(fmaxf(raw[4], raw[5]), fmaxf(raw[6], raw[7])));
-        x = fmaxf(x, __shfl_xor(x, 16, 64));
-        x = fmaxf(x, __shfl_xor(x, 32, 64));
-        const float m_new = fmaxf(m_ref[s], x);
-        const float alpha = __builtin_amdgcn_exp2f(m_ref[s] - m_new);
-        m_ref[s] = m_new;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float ar = __shfl(alpha, 4 * g + r, 64);
-          lsum[s][r] *= ar;
-#pragma unroll
-          for (int mf = 0; mf < 8; ++mf) acc[s][mf][r] *= ar;
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[e], scale_abs, -m_ref[s]));
-      }
-      if (DIAG) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (key_a + r > pos[s]) pe[r] = 0.f;
-          if (!has_b || key_b + r > pos[s]) pe[4 + r] = 0.f;
-        }
-      }
-      pw[s].x = ex_pack_bf16(pe[0], pe[1]);
-      pw[s].y = ex_pack_bf16(pe[2], pe[3]);
-      pw[s].z = ex_pack_bf16(pe[4], pe[5]);
-      pw[s].w = ex_pack_bf16(pe[6], pe[7]);
-      lsum[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(ones), lsum[s], 0, 0, 0);
-    }
-    uint4 live = make_uint4(~0u, ~0u, ~0u, ~0u);  // rows past the sequence may hold anything: their V is cleared
-    if (DIAG) {
-      live.x = (key_a + 0 < m ? 0x0000FFFFu : 0u) | (key_a + 1 < m ? 0xFFFF0000u : 0u);
-      live.y = (key_a + 2 < m ? 0x0000FFFFu : 0u) | (key_a + 3 < m ? 0xFFFF0000u : 0u);
-      live.z = has_b ? (key_b + 0 < m ? 0x0000FFFFu : 0u) | (key_b + 1 < m ? 0xFFFF0000u : 0u) : 0u;
-      live.w = has_b ? (key_b + 2 < m ? 0x0000FFFFu : 0u) | (key_b + 3 < m ? 0xFFFF0000u : 0u) : 0u;
-    }
-#pragma unroll
-    for (int mf = 0; mf < 8; ++mf) {
-      const uint2 ta = exl_read_tr(buf + v_off[mf]), tb = exl_read_tr(buf + EXL_TILE_BYTES + v_off[mf]);
-      uint4 col = make_uint4(ta.x, ta.y, tb.x, tb.y);
-      if (DIAG) col = make_uint4(col.x & live.x, col.y & live.y, col.z & live.z, col.w & live.w);
 #pragma unroll
       for (int s = 0; s < 2; ++s)
-        acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
+        lsum[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(ones), lsum[s], 0, 0, 0);
+      uint4 live = make_uint4(~0u, ~0u, ~0u, ~0u);  // rows past the sequence may hold anything: their V is cleared
+      if (DIAG) {
+        live.x = (key_a + 0 < m ? 0x0000FFFFu : 0u) | (key_a + 1 < m ? 0xFFFF0000u : 0u);
+        live.y = (key_a + 2 < m ? 0x0000FFFFu : 0u) | (key_a + 3 < m ? 0xFFFF0000u : 0u);
+        live.z = has_b ? (key_b + 0 < m ? 0x0000FFFFu : 0u) | (key_b + 1 < m ? 0xFFFF0000u : 0u) : 0u;
+        live.w = has_b ? (key_b + 2 < m ? 0x0000FFFFu : 0u) | (key_b + 3 < m ? 0xFFFF0000u : 0u) : 0u;
+      }
+      const exl_lds_ptr vbuf = lds3 + PAR * EXL_PAIR_BYTES;
+#pragma unroll
+      for (int mf = 0; mf < 8; ++mf) {
+        const int v_off = v_off0 ^ (mf << 5);
+        const uint2 ta = exl_read_tr(vbuf + v_off), tb = exl_read_tr(vbuf + EXL_TILE_BYTES + v_off);
+        uint4 col = make_uint4(ta.x, ta.y, tb.x, tb.y);
+        if (DIAG) col = make_uint4(col.x & live.x, col.y & live.y, col.z & live.z, col.w & live.w);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+          acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
+      }
     }
-  };
-  // Pair p is multiplied out of buffer p % 2 while pair p + 1 is copied into the other one, which every
-  // wave left at the barrier that ended pair p - 1.  All bounds are the same for the whole block.
-  auto step = [&](int p, auto diag_c, auto buf_c) {
-    constexpr int BUF = decltype(buf_c)::value;
-    if (p + 1 < n_pairs) {
-      copy_tile(pid_next, 1 - BUF);
-      pid_next = page_id(p + 2);
-    }
-    if (active && 2 * p * TIM_PS <= last_pos) pair(p, diag_c, buf_c);
     exl_wait_copies();
     __syncthreads();
   };
-  using exl_b0 = std::integral_constant<int, 0>;
-  using exl_b1 = std::integral_constant<int, 1>;
+  using exl_p0 = std::integral_constant<int, 0>;
+  using exl_p1 = std::integral_constant<int, 1>;
 
+  // fill the pipeline: K of pairs 0 and 1, V of pair 0; scores of pair 0
+  pid_next = page_id(0);
   copy_tile(pid_next, 0);
   pid_next = page_id(1);
+  if (k_wave) {
+    if (1 < n_pairs) copy_tile(pid_next, 1);
+    pid_next = page_id(2);
+  }
   exl_wait_copies();
   __syncthreads();
+  float raw_even[2][8], raw_odd[2][8];  // scores waiting to be weighted: of even pairs, of odd pairs (hot loop)
+  if (active) scores(exl_p0{}, raw_even);
+  __syncthreads();  // the first trip overwrites the K tiles just read
+  // All bounds are the same for the whole block.
   int p = 0;
-  for (; p + 2 <= n_full; p += 2) {  // two pairs per trip, so that the buffer is known at compile time
-    step(p, std::false_type{}, exl_b0{});
-    step(p + 1, std::false_type{}, exl_b1{});
+  for (; p + 2 <= n_full; p += 2) {  // two pairs per trip of the loop, so that the buffers are known at compile time
+    trip(p, std::false_type{}, exl_p0{}, raw_even, raw_odd);
+    trip(p + 1, std::false_type{}, exl_p1{}, raw_odd, raw_even);
   }
-  for (; p < n_pairs; ++p) {  // the last of the full pairs, if their number is odd, and the pairs at the diagonal
-    if (p & 1) step(p, std::true_type{}, exl_b1{});
-    else step(p, std::true_type{}, exl_b0{});
+  for (; p < n_pairs; ++p) {  // the last of the full pairs, if their number is odd, and the pairs at the diagonal:
+    trip(p, std::true_type{}, p & 1, raw_even, raw_odd);  // one instance, buffers chosen at run time
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) raw_even[s][e] = raw_odd[s][e];
   }
   if (!active) return;
 
