@@ -252,6 +252,7 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 // the copies is therefore written by hand before each barrier.
 #define EXL_TILE_BYTES TIM_TILE_BYTES
 #define EXL_PAIR_BYTES (2 * EXL_TILE_BYTES)  // one pair of pages of K, or of V
+#define EXL_RING 3                           // pairs of K, and of V, in LDS: one in use, two on their way
 
 typedef __attribute__((address_space(3))) unsigned char *exl_lds_ptr;
 typedef short exl_s16x4 __attribute__((ext_vector_type(4)));
@@ -261,6 +262,8 @@ __device__ __forceinline__ void exl_copy16(const void *src, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
 }
 __device__ __forceinline__ void exl_wait_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// all but the four youngest copies of this wave (memory operations complete in order)
+__device__ __forceinline__ void exl_wait_older_copies() { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
 
 typedef unsigned int exl_u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 exl_read16(exl_lds_ptr p) {
@@ -276,7 +279,7 @@ __global__ void __launch_bounds__(EX_THREADS, 2)
 tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer,
                            const uint4 *__restrict__ q_ext, void *__restrict__ out_ext, int n_ext_total,
                            float scale_log2) {
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * EXL_PAIR_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * EXL_RING * EXL_PAIR_BYTES];
   const int kvh = blockIdx.x;
   if (!pl.totals[TIM_TOT_OK] || (int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
   const int tile = pl.totals[TIM_TOT_EXT_TILES] - 1 - blockIdx.y;
@@ -336,8 +339,10 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
-  // ---- LDS: K of pairs p + 1 and p + 2, V of pairs p and p + 1 (the scores run one pair ahead of
-  // the products): [K parity 0: page A, page B][K parity 1][V parity 0][V parity 1], 8 KiB each
+  // ---- LDS: a ring of EXL_RING pairs of K tiles and one of V tiles, 8 KiB (page A, page B) per pair;
+  // pair q lives in slot q % EXL_RING of each.  While pair p is weighted, K holds pairs p + 1 (read),
+  // p + 2 (arrived or arriving) and p + 3 (requested now), V holds p, p + 1, p + 2 likewise: a copy has
+  // two trips of the loop to arrive.
   // ---- the copy side: waves 0 and 1 bring K pages A and B, waves 2 and 3 bring V pages A and B
   const int ws = __builtin_amdgcn_readfirstlane(w);
   const bool k_wave = ws < 2;
@@ -349,17 +354,20 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
     src_unit[i] = r * 16 + (k_wave ? slot ^ r : slot ^ ((r & 7) << 1));
   }
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
-  const uint32_t copy_base = lds_base + (k_wave ? 0 : 2 * EXL_PAIR_BYTES) + (ws & 1) * EXL_TILE_BYTES;
-  // The page id of a tile is read one pair before the tile itself, so that its latency is not in the way.
-  auto page_id = [&](int pair_) { return ptab[min(2 * pair_ + (ws & 1), last_page)]; };
-  auto copy_tile = [&](int pid, int parity) {
-    int phys = __builtin_amdgcn_readfirstlane(pid);
+  const uint32_t copy_base = lds_base + (k_wave ? 0 : EXL_RING * EXL_PAIR_BYTES) + (ws & 1) * EXL_TILE_BYTES;
+  // Page ids: lane l of pid_vec holds the id of this wave's page of pair pid_base + l; one load per 64 pairs
+  // keeps the loop free of global loads (whose waits would also wait for the copies in flight).
+  auto load_pids = [&](int base) { return ptab[min(2 * (base + lane) + (ws & 1), last_page)]; };
+  int pid_base = 0;
+  int pid_vec = load_pids(0);
+  auto copy_tile = [&](int pair_, int slot) {  // pair_ in [pid_base, pid_base + 64)
+    int phys = __builtin_amdgcn_readlane(pid_vec, pair_ - pid_base);
     if (phys < 0 || phys >= cfg.num_pages) {
       tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
       phys = 0;
     }
     const uint4 *src = tile_pool + ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-    const uint32_t dst = copy_base + parity * EXL_PAIR_BYTES;
+    const uint32_t dst = copy_base + slot * EXL_PAIR_BYTES;
     exl_copy16(src + src_unit[0], dst);
     exl_copy16(src + src_unit[1], dst + 1024);
     exl_copy16(src + src_unit[2], dst + 2048);
@@ -373,12 +381,11 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   for (int step = 0; step < 4; ++step) k_off[step] = n * 256 + (((4 * step + g) ^ n) << 4);
   // V: row r = 4 g + n / 4, unit mf ^ (r % 8), piece n % 4; the unit is three address bits of their own,
   // so the offset for column block mf is v_off0 ^ (mf << 5)
-  const int v_off0 = 2 * EXL_PAIR_BYTES + (4 * g + (n >> 2)) * 256 + (((4 * g + (n >> 2)) & 7) << 5) + 8 * (n & 3);
+  const int v_off0 = EXL_RING * EXL_PAIR_BYTES + (4 * g + (n >> 2)) * 256 + (((4 * g + (n >> 2)) & 7) << 5) + 8 * (n & 3);
 
-  // scores of the pair whose K lies in the K buffer of parity PAR: both row sets, raw (unscaled, unmasked)
-  auto scores = [&](auto par_c, float (&raw)[2][8]) {
-    const int PAR = par_c;  // a compile-time constant in the hot loop
-    const exl_lds_ptr buf = lds3 + PAR * EXL_PAIR_BYTES;
+  // scores of the pair whose K lies in the given slot of the K ring: both row sets, raw (unscaled, unmasked)
+  auto scores = [&](int slot, float (&raw)[2][8]) {
+    const exl_lds_ptr buf = lds3 + slot * EXL_PAIR_BYTES;
     ex_f32x4 sa[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, sb[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
     for (int step = 0; step < 4; ++step) {  // four independent accumulation chains; K operands live one step only
@@ -401,29 +408,34 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
       }
   };
 
-  // One trip of the pipeline, pair p of parity PAR = p % 2: the scores of pair p + 1 go through the matrix
+  // One trip of the pipeline, pair p, s0 = p % EXL_RING: the scores of pair p + 1 go through the matrix
   // cores while the vector units turn the scores of pair p (in `cur`) into weights; then the products of
-  // pair p.  Meanwhile K of pair p + 2 and V of pair p + 1 are copied in.  DIAG: pair p may hold keys
-  // beyond some row's own position, rows past the sequence, or no second page (the DIAG instance is also
-  // correct for any other pair, only slower).
+  // pair p.  K of pair p + 3 and V of pair p + 2 are requested.  DIAG: pair p may hold keys beyond some
+  // row's own position, rows past the sequence, or no second page (the DIAG instance is also correct for
+  // any other pair, only slower).
   //
   // Lazy reference maximum, checked on the weights: they are first computed against the current
   // reference; only if one of them exceeds 2^EX_LAZY_MAX (always on the first pair: every weight is then
   // infinite) is the reference renewed from the scores, the accumulators rescaled and the weights redone.
-  int pid_next;
-  auto trip = [&](int p, auto diag_c, auto par_c, float (&cur)[2][8], float (&nxt)[2][8]) {
+  auto trip = [&](int p, int s0, auto diag_c, float (&cur)[2][8], float (&nxt)[2][8]) {
     constexpr bool DIAG = decltype(diag_c)::value;
-    const int PAR = par_c;  // a compile-time constant in the hot loop
-    {
-      const int cp = p + (k_wave ? 2 : 1);  // K of pair p + 2 into K parity PAR, V of pair p + 1 into V parity 1 - PAR;
-      if (cp < n_pairs) copy_tile(pid_next, k_wave ? PAR : 1 - PAR);  // every wave left those at the last barrier
-      pid_next = page_id(cp + 1);
+    const int s1 = s0 == EXL_RING - 1 ? 0 : s0 + 1, s2 = s1 == EXL_RING - 1 ? 0 : s1 + 1;
+    // K of pair p + 3 takes the slot of pair p, V of pair p + 2 that of pair p - 1: every wave left both
+    // at the last barrier
+    const int cp = p + (k_wave ? 3 : 2);
+    const bool copied = cp < n_pairs;
+    if (copied) {
+      if (cp - pid_base == 64) {
+        pid_base = cp;
+        pid_vec = load_pids(cp);
+      }
+      copy_tile(cp, k_wave ? s0 : s2);
     }
     if (active) {
       const int pg = 2 * p;
       const bool has_b = !DIAG || pg + 1 <= last_page;
       const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
-      scores(1 - PAR, nxt);  // past the last pair this reads stale tiles; unused
+      scores(s1, nxt);  // past the last pair this reads stale tiles; unused
       // weights of set s against the current reference, packed; returns their largest
       auto weights = [&](int s, uint4 &packed) {
         float pe[8];
@@ -484,7 +496,7 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
         live.z = has_b ? (key_b + 0 < m ? 0x0000FFFFu : 0u) | (key_b + 1 < m ? 0xFFFF0000u : 0u) : 0u;
         live.w = has_b ? (key_b + 2 < m ? 0x0000FFFFu : 0u) | (key_b + 3 < m ? 0xFFFF0000u : 0u) : 0u;
       }
-      const exl_lds_ptr vbuf = lds3 + PAR * EXL_PAIR_BYTES;
+      const exl_lds_ptr vbuf = lds3 + s0 * EXL_PAIR_BYTES;
 #pragma unroll
       for (int mf = 0; mf < 8; ++mf) {
         const int v_off = v_off0 ^ (mf << 5);
@@ -496,33 +508,35 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
           acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
       }
     }
-    exl_wait_copies();
+    // what the next trip reads was requested one trip ago: only this trip's four copies may still be under way
+    if (copied) exl_wait_older_copies();
+    else exl_wait_copies();
     __syncthreads();
   };
-  using exl_p0 = std::integral_constant<int, 0>;
-  using exl_p1 = std::integral_constant<int, 1>;
 
-  // fill the pipeline: K of pairs 0 and 1, V of pair 0; scores of pair 0
-  pid_next = page_id(0);
-  copy_tile(pid_next, 0);
-  pid_next = page_id(1);
-  if (k_wave) {
-    if (1 < n_pairs) copy_tile(pid_next, 1);
-    pid_next = page_id(2);
-  }
+  // fill the pipeline: K of pairs 0, 1 and 2, V of pairs 0 and 1; scores of pair 0
+  for (int q = 0; q < (k_wave ? 3 : 2); ++q)
+    if (q < n_pairs) copy_tile(q, q);
   exl_wait_copies();
   __syncthreads();
   float raw_even[2][8], raw_odd[2][8];  // scores waiting to be weighted: of even pairs, of odd pairs (hot loop)
-  if (active) scores(exl_p0{}, raw_even);
+  if (active) scores(0, raw_even);
   __syncthreads();  // the first trip overwrites the K tiles just read
   // All bounds are the same for the whole block.
-  int p = 0;
-  for (; p + 2 <= n_full; p += 2) {  // two pairs per trip of the loop, so that the buffers are known at compile time
-    trip(p, std::false_type{}, exl_p0{}, raw_even, raw_odd);
-    trip(p + 1, std::false_type{}, exl_p1{}, raw_odd, raw_even);
+  int p = 0, s0 = 0;  // s0 = p % EXL_RING
+  auto advance = [&]() {
+    ++p;
+    s0 = s0 == EXL_RING - 1 ? 0 : s0 + 1;
+  };
+  while (p + 2 <= n_full) {  // two pairs per trip of the loop: the two score arrays swap roles without copies
+    trip(p, s0, std::false_type{}, raw_even, raw_odd);
+    advance();
+    trip(p, s0, std::false_type{}, raw_odd, raw_even);
+    advance();
   }
-  for (; p < n_pairs; ++p) {  // the last of the full pairs, if their number is odd, and the pairs at the diagonal:
-    trip(p, std::true_type{}, p & 1, raw_even, raw_odd);  // one instance, buffers chosen at run time
+  while (p < n_pairs) {  // the last of the full pairs, if their number is odd, and the pairs at the diagonal
+    trip(p, s0, std::true_type{}, raw_even, raw_odd);
+    advance();
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
