@@ -228,11 +228,22 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 // operands from there.  Two LDS buffers: the copies of the next pair are in flight while this
 // pair is multiplied, and one barrier per pair separates readers from the next writer.
 //
-// Operands.  K (A operand of the score product) is read as "row n, 16-byte chunk 4 s + g".
-// V (B operand of the output product) is read with the transposing LDS load: lanes (g, j)
-// point at row 4 g + j / 4, dims 16 mf + 4 (j % 4) .. +3, and lane (g, n) receives
-// V[4 g + e][16 mf + n], e = 0..3, which together with the same read of the second page is
-// the B operand for output columns 16 mf .. 16 mf + 15.  No transposition in registers.
+// Matrix instruction.  The 32x32x16 bf16 MFMA, not the 16x16x32 one of the decode kernel:
+// a loop of nothing but independent MFMAs sustains 1.8-2.1 PFLOP/s with the former and
+// 1.36 PFLOP/s with the latter on this chip (measured; nominal peak 2.5).  A wave's 32 query
+// rows (8 tokens x 4 heads) are exactly one 32-wide operand, a pair of pages the other.
+//
+// Operands.  Lane l = 32 h + j.  Scores S^T = K . Q^T: A operand = K, lane (h, j) reads key j
+// of the pair (page j / 16, row j % 16), 16-byte chunk 2 t + h for step t of 8; B operand =
+// Q, the lane's own query row j, same chunk.  The result has, in register r of lane (h, j),
+// the score of row j against key 8 (r / 4) + 4 h + r % 4: a query row's 16 scores per half
+// wave sit in one lane, so the softmax arithmetic is lane-local and the weights, packed, are
+// directly the A operand of the output product (registers 0..7: page A, 8..15: page B).
+// Its B operand, V, is read with the transposing LDS load: each group of 16 lanes points at
+// four rows x 16 dims, and lane (h, j) receives V[4 h + x][32 c + j], x = 0..3, and with a
+// second read the same of rows + 8: the 8 keys that the weights' registers hold.  No
+// transposition in registers.  Output O: register r of lane (h, j) holds row
+// 8 (r / 4) + 4 h + r % 4, dim 32 c + j of block c.
 //
 // Bank conflicts.  Measured on this chip: a 16-byte-per-lane LDS read is served 16 lanes at a
 // time, and the lanes served together are not consecutive: of lanes 0..31 they are
@@ -240,9 +251,8 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 // conflict-free when its 16-byte slots differ modulo 256 bytes.  For K, chunk c of row r is
 // stored at slot c ^ r, which makes the slots of each group a permutation of 0..15.  (Rows
 // padded to 272 bytes, the usual remedy, collide two-way under this grouping.)  For V, the
-// 32-byte unit u of row r is stored at unit u ^ (r % 8): the eight rows that a transposing
-// read touches per half-wave then lie in eight different 32-byte bank groups (measured
-// conflict-free; unswizzled the same read is 3.5 times slower).  The copy into LDS writes
+// 64-byte unit u of row r is stored at unit u ^ (r % 4): the four rows that a transposing
+// read touches per half-wave then lie in four different 64-byte bank groups.  The copy into LDS writes
 // 1 KiB (4 rows) per instruction in lane order, so the swizzle is applied on the global
 // side: each lane fetches the chunk that belongs in its slot.
 //
@@ -256,6 +266,7 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
 
 typedef __attribute__((address_space(3))) unsigned char *exl_lds_ptr;
 typedef short exl_s16x4 __attribute__((ext_vector_type(4)));
+typedef float exl_f32x16 __attribute__((ext_vector_type(16)));
 
 // 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base is wave-uniform)
 __device__ __forceinline__ void exl_copy16(const void *src, uint32_t lds_base) {
@@ -292,47 +303,41 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   if (hdr[TIM_HDR_BAD]) return;  // uniform for the block, like every exit before the barriers
   const int b = hdr[TIM_HDR_SEQ], m = hdr[TIM_HDR_N_KEPT], f = hdr[TIM_HDR_FIRST_PRUNED];
   const int ext = hdr[TIM_HDR_EXT], ext_off = hdr[TIM_HDR_EXT_OFF];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, n = lane & 15;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, h = lane >> 5, j = lane & 31;
   const int blk_tok0 = (tile - hdr[TIM_HDR_EXT_TILE_OFF]) * EX_TILE_TOKENS;
   const int tok0 = blk_tok0 + w * EX_WAVE_TOKENS;
   const bool active = tok0 < ext;  // a wave without a token still copies and meets the barriers
 
-  // B operands of the score product: column n of set s is (token 4 s + n / 4, head n % 4).
+  // B operands of the score product: this lane's query row j = (token j / 4, head j % 4), chunks 2 t + h.
   // A negative scale is applied as |scale| to -q, which is exact.
   const uint32_t q_flip = scale_log2 < 0.f ? 0x80008000u : 0u;
   const float scale_abs = fabsf(scale_log2);
-  uint4 qb[2][4];
-  int pos[2];
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const int tl = tok0 + 4 * s + (n >> 2);
+  uint4 qb[8];
+  int pos;  // position of the lane's query row; -1: no such row
+  {
+    const int tl = tok0 + (j >> 2);
     const bool ok = tl < ext && ext_off + tl < n_ext_total;
-    pos[s] = ok ? f + tl : -1;
+    pos = ok ? f + tl : -1;
 #pragma unroll
-    for (int step = 0; step < 4; ++step) {
+    for (int t = 0; t < 8; ++t) {
       uint4 q = make_uint4(0, 0, 0, 0);
-      if (ok) q = q_ext[((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + (n & 3)) * 16 + 4 * step + g];
-      qb[s][step] = make_uint4(q.x ^ q_flip, q.y ^ q_flip, q.z ^ q_flip, q.w ^ q_flip);
+      if (ok) q = q_ext[((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + (j & 3)) * 16 + 2 * t + h];
+      qb[t] = make_uint4(q.x ^ q_flip, q.y ^ q_flip, q.z ^ q_flip, q.w ^ q_flip);
     }
   }
   const int blk_first_pos = f + blk_tok0;
-  const int last_pos = f + min(tok0 + EX_WAVE_TOKENS, ext) - 1;  // this wave's largest position
   // block-uniform: the pairs of pages the block walks, and how many of them lie wholly at or
   // before its first position (no mask, no stale row, both pages present)
   const int last_page = (f + min(blk_tok0 + EX_TILE_TOKENS, ext) - 1) / TIM_PS;
   const int n_pairs = last_page / 2 + 1;
   const int n_full = min(n_pairs, (blk_first_pos + 1) / (2 * TIM_PS));
 
-  // The softmax denominators come from the matrix cores too: P times a column of ones, in the
-  // same layout (row 4 g + r in register r) as the output accumulators.
-  const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
-  float m_ref[2] = {EX_NEG_BIG, EX_NEG_BIG};
-  ex_f32x4 lsum[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  ex_f32x4 acc[2][8];
+  float m_ref = EX_NEG_BIG, l_part = 0.f;  // of the lane's row j; l_part covers the keys of this half wave
+  exl_f32x16 acc[4];
 #pragma unroll
-  for (int s = 0; s < 2; ++s)
+  for (int c = 0; c < 4; ++c)
 #pragma unroll
-    for (int mf = 0; mf < 8; ++mf) acc[s][mf] = (ex_f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
 
   const uint4 *kpool = reinterpret_cast<const uint4 *>(st.k_pool);
   const uint4 *vpool = reinterpret_cast<const uint4 *>(st.v_pool);
@@ -351,7 +356,7 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int r = 4 * i + (lane >> 4), slot = lane & 15;
-    src_unit[i] = r * 16 + (k_wave ? slot ^ r : slot ^ ((r & 7) << 1));
+    src_unit[i] = r * 16 + (k_wave ? slot ^ r : slot ^ ((r & 3) << 2));
   }
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
   const uint32_t copy_base = lds_base + (k_wave ? 0 : EXL_RING * EXL_PAIR_BYTES) + (ws & 1) * EXL_TILE_BYTES;
@@ -376,36 +381,31 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
 
   // ---- the read side: LDS offsets of this lane's operands within a pair's 8 KiB
   const exl_lds_ptr lds3 = (exl_lds_ptr)lds;
-  int k_off[4];
-#pragma unroll
-  for (int step = 0; step < 4; ++step) k_off[step] = n * 256 + (((4 * step + g) ^ n) << 4);
-  // V: row r = 4 g + n / 4, unit mf ^ (r % 8), piece n % 4; the unit is three address bits of their own,
-  // so the offset for column block mf is v_off0 ^ (mf << 5)
-  const int v_off0 = EXL_RING * EXL_PAIR_BYTES + (4 * g + (n >> 2)) * 256 + (((4 * g + (n >> 2)) & 7) << 5) + 8 * (n & 3);
+  // K: key j = (page j / 16, row j % 16), chunk (2 t + h) ^ row.  The step is three address bits of their
+  // own (5..7), so the offset of step t is k_off0 ^ (t << 5).
+  const int k_off0 = (j >> 4) * EXL_TILE_BYTES + (j & 15) * 256 + ((h ^ (j & 15)) << 4);
+  // V: the 16 lanes of group G = lane / 16 point at rows 4 h + jj / 4 (jj = lane % 16), dims
+  // 32 c + 16 (G % 2) + 4 (jj % 4) .. + 3, i.e. 64-byte unit c of the row, stored at unit c ^ (row % 4).
+  // The unit is two address bits of their own (6..7): offset of block c = v_off0 ^ (c << 6).
+  const int v_row = 4 * h + ((lane & 15) >> 2);
+  const int v_off0 = EXL_RING * EXL_PAIR_BYTES + v_row * 256 + ((v_row & 3) << 6) + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
 
-  // scores of the pair whose K lies in the given slot of the K ring: both row sets, raw (unscaled, unmasked)
-  auto scores = [&](int slot, float (&raw)[2][8]) {
+  // The A operands of a pair's score product, from the given slot of the K ring.
+  auto read_k = [&](int slot, uint4 (&ka)[8]) {
     const exl_lds_ptr buf = lds3 + slot * EXL_PAIR_BYTES;
-    ex_f32x4 sa[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, sb[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int step = 0; step < 4; ++step) {  // four independent accumulation chains; K operands live one step only
-      // LDS reads may not be moved up across this point (everything else may): otherwise all eight K
-      // operands are fetched first and the kernel runs out of registers
-      if (step == 2) __builtin_amdgcn_sched_barrier(0x7F);
-      const uint4 ka = exl_read16(buf + k_off[step]), kb = exl_read16(buf + EXL_TILE_BYTES + k_off[step]);
+    for (int t = 0; t < 8; ++t) ka[t] = exl_read16(buf + (k_off0 ^ (t << 5)));
+  };
+  // scores, raw (unscaled, unmasked): raw[r] = row j against key 8 (r / 4) + 4 h + r % 4 of the pair
+  auto scores = [&](const uint4 (&ka)[8], float (&raw)[16]) {
+    exl_f32x16 sc;
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        sa[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(ka), ex_as_bf16x8(qb[s][step]), sa[s], 0, 0, 0);
-        sb[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(kb), ex_as_bf16x8(qb[s][step]), sb[s], 0, 0, 0);
-      }
-    }
+    for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int t = 0; t < 8; ++t)
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ex_as_bf16x8(ka[t]), ex_as_bf16x8(qb[t]), sc, 0, 0, 0);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        raw[s][r] = sa[s][r];
-        raw[s][4 + r] = sb[s][r];
-      }
+    for (int r = 0; r < 16; ++r) raw[r] = sc[r];
   };
 
   // One trip of the pipeline, pair p, s0 = p % EXL_RING: the scores of pair p + 1 go through the matrix
@@ -417,9 +417,14 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
   // Lazy reference maximum, checked on the weights: they are first computed against the current
   // reference; only if one of them exceeds 2^EX_LAZY_MAX (always on the first pair: every weight is then
   // infinite) is the reference renewed from the scores, the accumulators rescaled and the weights redone.
-  auto trip = [&](int p, int s0, auto diag_c, float (&cur)[2][8], float (&nxt)[2][8]) {
+  auto trip = [&](int p, int s0, auto diag_c, float (&cur)[16], float (&nxt)[16]) {
     constexpr bool DIAG = decltype(diag_c)::value;
     const int s1 = s0 == EXL_RING - 1 ? 0 : s0 + 1, s2 = s1 == EXL_RING - 1 ? 0 : s1 + 1;
+    // The operands are fetched from LDS as early as the code allows, in basic blocks of their own, because the
+    // compiler otherwise puts each read right in front of its use: K of pair p + 1 here, V of pair p before
+    // the check of the maximum.  (Past the last pair this reads stale tiles; the scores are not used.)
+    uint4 ka[8];
+    read_k(s1, ka);
     // K of pair p + 3 takes the slot of pair p, V of pair p + 2 that of pair p - 1: every wave left both
     // at the last barrier
     const int cp = p + (k_wave ? 3 : 2);
@@ -432,81 +437,89 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
       copy_tile(cp, k_wave ? s0 : s2);
     }
     if (active) {
-      const int pg = 2 * p;
-      const bool has_b = !DIAG || pg + 1 <= last_page;
-      const int key_a = pg * TIM_PS + 4 * g, key_b = key_a + TIM_PS;
-      scores(s1, nxt);  // past the last pair this reads stale tiles; unused
-      // weights of set s against the current reference, packed; returns their largest
-      auto weights = [&](int s, uint4 &packed) {
-        float pe[8];
+      const int key0 = 2 * p * TIM_PS + 4 * h;  // key of register r: key0 + 8 (r / 4) + r % 4
+      const bool has_b = !DIAG || 2 * p + 1 <= last_page;
+      scores(ka, nxt);
+      // weights of the lane's row against the current reference, packed: pw[u] covers page u; returns the largest
+      uint4 pw[2];
+      auto weights = [&]() {
+        float pe[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pe[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[s][e], scale_abs, -m_ref[s]));
-        const float top = fmaxf(fmaxf(fmaxf(pe[0], pe[1]), fmaxf(pe[2], pe[3])), fmaxf(fmaxf(pe[4], pe[5]), fmaxf(pe[6], pe[7])));
+        for (int r = 0; r < 16; ++r) pe[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[r], scale_abs, -m_ref));
+        const float top = fmaxf(fmaxf(fmaxf(fmaxf(pe[0], pe[1]), fmaxf(pe[2], pe[3])), fmaxf(fmaxf(pe[4], pe[5]), fmaxf(pe[6], pe[7]))),
+                                fmaxf(fmaxf(fmaxf(pe[8], pe[9]), fmaxf(pe[10], pe[11])), fmaxf(fmaxf(pe[12], pe[13]), fmaxf(pe[14], pe[15]))));
         if (DIAG) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            if (key_a + r > pos[s]) pe[r] = 0.f;
-            if (!has_b || key_b + r > pos[s]) pe[4 + r] = 0.f;
-          }
+          for (int r = 0; r < 16; ++r)
+            if (key0 + 8 * (r >> 2) + (r & 3) > pos || (r >= 8 && !has_b)) pe[r] = 0.f;
         }
-        packed.x = ex_pack_bf16(pe[0], pe[1]);
-        packed.y = ex_pack_bf16(pe[2], pe[3]);
-        packed.z = ex_pack_bf16(pe[4], pe[5]);
-        packed.w = ex_pack_bf16(pe[6], pe[7]);
-        return top;
+        const float sum = (((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]))) +
+                          (((pe[8] + pe[9]) + (pe[10] + pe[11])) + ((pe[12] + pe[13]) + (pe[14] + pe[15])));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          pw[u].x = ex_pack_bf16(pe[8 * u + 0], pe[8 * u + 1]);
+          pw[u].y = ex_pack_bf16(pe[8 * u + 2], pe[8 * u + 3]);
+          pw[u].z = ex_pack_bf16(pe[8 * u + 4], pe[8 * u + 5]);
+          pw[u].w = ex_pack_bf16(pe[8 * u + 6], pe[8 * u + 7]);
+        }
+        return make_float2(top, sum);
       };
       if (DIAG) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {  // a masked score is a large negative finite number: it survives a zero scale
-            if (key_a + r > pos[s]) cur[s][r] = EX_NEG_BIG;
-            if (!has_b || key_b + r > pos[s]) cur[s][4 + r] = EX_NEG_BIG;
-          }
+        for (int r = 0; r < 16; ++r)  // a masked score is a large negative finite number: it survives a zero scale
+          if (key0 + 8 * (r >> 2) + (r & 3) > pos || (r >= 8 && !has_b)) cur[r] = EX_NEG_BIG;
       }
-      uint4 pw[2];
-      const float pmax = fmaxf(weights(0, pw[0]), weights(1, pw[1]));
-      if (__any(pmax > EX_LAZY_LIMIT)) {
+      const exl_lds_ptr vbuf = lds3 + s0 * EXL_PAIR_BYTES;
+      uint4 col[4][2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          float x = scale_abs * fmaxf(fmaxf(fmaxf(cur[s][0], cur[s][1]), fmaxf(cur[s][2], cur[s][3])),
-                                      fmaxf(fmaxf(cur[s][4], cur[s][5]), fmaxf(cur[s][6], cur[s][7])));
-          x = fmaxf(x, __shfl_xor(x, 16, 64));
-          x = fmaxf(x, __shfl_xor(x, 32, 64));
-          const float m_new = fmaxf(m_ref[s], x);
-          const float alpha = __builtin_amdgcn_exp2f(m_ref[s] - m_new);
-          m_ref[s] = m_new;
+      for (int c = 0; c < 4; ++c)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float ar = __shfl(alpha, 4 * g + r, 64);
-            lsum[s][r] *= ar;
+        for (int u = 0; u < 2; ++u) {
+          const exl_lds_ptr at = vbuf + u * EXL_TILE_BYTES + (v_off0 ^ (c << 6));
+          const uint2 ta = exl_read_tr(at), tb = exl_read_tr(at + 8 * 256);
+          col[c][u] = make_uint4(ta.x, ta.y, tb.x, tb.y);
+        }
+      float2 ts = weights();
+      if (__any(ts.x > EX_LAZY_LIMIT)) {
+        float x = cur[0];
 #pragma unroll
-            for (int mf = 0; mf < 8; ++mf) acc[s][mf][r] *= ar;
-          }
-          weights(s, pw[s]);
+        for (int r = 1; r < 16; ++r) x = fmaxf(x, cur[r]);
+        x *= scale_abs;
+        x = fmaxf(x, __shfl_xor(x, 32, 64));  // the other half of the row's keys
+        const float m_new = fmaxf(m_ref, x);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        m_ref = m_new;
+        l_part *= alpha;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {  // the accumulators hold other rows than the lane's own
+          const float ar = __shfl(alpha, 8 * (r >> 2) + 4 * h + (r & 3), 64);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[c][r] *= ar;
+        }
+        ts = weights();
+      }
+      l_part += ts.y;
+      uint4 live[2] = {make_uint4(~0u, ~0u, ~0u, ~0u), make_uint4(~0u, ~0u, ~0u, ~0u)};
+      if (DIAG) {  // rows past the sequence may hold anything: their V is cleared (element e of the operand:
+                   // key 16 u + 8 (e / 4) + 4 h + e % 4 of the pair)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int k = key0 + 16 * u;
+          const bool pg_ok = u == 0 || has_b;
+          live[u].x = (pg_ok && k + 0 < m ? 0x0000FFFFu : 0u) | (pg_ok && k + 1 < m ? 0xFFFF0000u : 0u);
+          live[u].y = (pg_ok && k + 2 < m ? 0x0000FFFFu : 0u) | (pg_ok && k + 3 < m ? 0xFFFF0000u : 0u);
+          live[u].z = (pg_ok && k + 8 < m ? 0x0000FFFFu : 0u) | (pg_ok && k + 9 < m ? 0xFFFF0000u : 0u);
+          live[u].w = (pg_ok && k + 10 < m ? 0x0000FFFFu : 0u) | (pg_ok && k + 11 < m ? 0xFFFF0000u : 0u);
         }
       }
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
-        lsum[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(ones), lsum[s], 0, 0, 0);
-      uint4 live = make_uint4(~0u, ~0u, ~0u, ~0u);  // rows past the sequence may hold anything: their V is cleared
-      if (DIAG) {
-        live.x = (key_a + 0 < m ? 0x0000FFFFu : 0u) | (key_a + 1 < m ? 0xFFFF0000u : 0u);
-        live.y = (key_a + 2 < m ? 0x0000FFFFu : 0u) | (key_a + 3 < m ? 0xFFFF0000u : 0u);
-        live.z = has_b ? (key_b + 0 < m ? 0x0000FFFFu : 0u) | (key_b + 1 < m ? 0xFFFF0000u : 0u) : 0u;
-        live.w = has_b ? (key_b + 2 < m ? 0x0000FFFFu : 0u) | (key_b + 3 < m ? 0xFFFF0000u : 0u) : 0u;
-      }
-      const exl_lds_ptr vbuf = lds3 + s0 * EXL_PAIR_BYTES;
+      for (int c = 0; c < 4; ++c)
 #pragma unroll
-      for (int mf = 0; mf < 8; ++mf) {
-        const int v_off = v_off0 ^ (mf << 5);
-        const uint2 ta = exl_read_tr(vbuf + v_off), tb = exl_read_tr(vbuf + EXL_TILE_BYTES + v_off);
-        uint4 col = make_uint4(ta.x, ta.y, tb.x, tb.y);
-        if (DIAG) col = make_uint4(col.x & live.x, col.y & live.y, col.z & live.z, col.w & live.w);
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-          acc[s][mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ex_as_bf16x8(pw[s]), ex_as_bf16x8(col), acc[s][mf], 0, 0, 0);
-      }
+        for (int u = 0; u < 2; ++u) {
+          uint4 x = col[c][u];
+          if (DIAG) x = make_uint4(x.x & live[u].x, x.y & live[u].y, x.z & live[u].z, x.w & live[u].w);
+          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ex_as_bf16x8(pw[u]), ex_as_bf16x8(x), acc[c], 0, 0, 0);
+        }
     }
     // what the next trip reads was requested one trip ago: only this trip's four copies may still be under way
     if (copied) exl_wait_older_copies();
@@ -519,8 +532,12 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
     if (q < n_pairs) copy_tile(q, q);
   exl_wait_copies();
   __syncthreads();
-  float raw_even[2][8], raw_odd[2][8];  // scores waiting to be weighted: of even pairs, of odd pairs (hot loop)
-  if (active) scores(0, raw_even);
+  float raw_even[16], raw_odd[16];  // scores waiting to be weighted: of even pairs, of odd pairs (hot loop)
+  if (active) {
+    uint4 ka[8];
+    read_k(0, ka);
+    scores(ka, raw_even);
+  }
   __syncthreads();  // the first trip overwrites the K tiles just read
   // All bounds are the same for the whole block.
   int p = 0, s0 = 0;  // s0 = p % EXL_RING
@@ -538,27 +555,25 @@ tim_extend_attn_lds_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs
     trip(p, s0, std::true_type{}, raw_even, raw_odd);
     advance();
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) raw_even[s][e] = raw_odd[s][e];
+    for (int r = 0; r < 16; ++r) raw_even[r] = raw_odd[r];
   }
   if (!active) return;
 
-  // lane (g, n) holds, for row (token 4 s + g, head r), output columns 16 mf + n
+  // register r of lane (h, j) holds row i = 8 (r / 4) + 4 h + r % 4 = (token i / 4, head i % 4), dim 32 c + j;
+  // the row's denominator is the sum of the two partial ones in lanes i and i + 32
+  const float l_row = l_part + __shfl_xor(l_part, 32, 64);
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    const int tl = tok0 + 4 * s + g;
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * h + (r & 3);
+    const float inv = 1.f / __shfl(l_row, i, 64);
+    const int tl = tok0 + (i >> 2);
     if (!(tl < ext && ext_off + tl < n_ext_total)) continue;
+    const int64_t o = ((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + (i & 3)) * TIM_D + j;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float inv = 1.f / lsum[s][r];
-      const int64_t o = ((int64_t)(ext_off + tl) * cfg.q_heads + kvh * TIM_G + r) * TIM_D + n;
-#pragma unroll
-      for (int mf = 0; mf < 8; ++mf) {
-        const float y = acc[s][mf][r] * inv;
-        if (OUT_BF16) reinterpret_cast<__bf16 *>(out_ext)[o + 16 * mf] = (__bf16)y;
-        else reinterpret_cast<float *>(out_ext)[o + 16 * mf] = y;
-      }
+    for (int c = 0; c < 4; ++c) {
+      const float y = acc[c][r] * inv;
+      if (OUT_BF16) reinterpret_cast<__bf16 *>(out_ext)[o + 32 * c] = (__bf16)y;
+      else reinterpret_cast<float *>(out_ext)[o + 32 * c] = y;
     }
   }
 }
