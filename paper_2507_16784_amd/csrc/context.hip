@@ -24,9 +24,6 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   c->attn_impl = 1;
   c->attn_cpb = 4;
   c->attn_fill = 2;
-  c->extend_lds = 1;
-  if (const char *v = std::getenv("TIM_EXTEND_LDS"))  // A-B measurement only
-    c->extend_lds = std::atoi(v) != 0;
   if (const char *v = std::getenv("TIM_ATTN_FILL")) {  // tuning experiments only
     const int x = std::atoi(v);
     if (x >= 1 && x <= 64) c->attn_fill = x;

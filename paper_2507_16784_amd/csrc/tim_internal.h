@@ -22,7 +22,6 @@ struct tim_ctx {
   int attn_impl;  // 1 = matrix-core attention (default), 0 = vector-ALU attention
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
-  int extend_lds; // 1 = extend attention stages K/V through LDS (default), 0 = every wave loads its own
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
   int timing_n = 0;
