@@ -369,6 +369,52 @@ def test_extend_attention_after_flush(gb, case):
         assert gpu.status() == 0
 
 
+def test_extend_attention_long_context_and_scales(gb):
+    """Extend attention over contexts of more than 128 pairs of pages (the kernel fetches its page ids
+    64 pairs at a time and keeps three pairs in flight), next to a short and a ragged sequence, with
+    positive, zero and negative softmax scale.  Sampled rows of the long sequence and every row of the
+    others are compared with the definition."""
+    from oracle import attention, bf16
+    from paper_2507_16784_amd.workload import tensors
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    tr = Trace(6000, [], [], [], [], [], [], [])
+    p0s = [4700, 90, 1000]
+    wl = Workload([tr, tr, tr], p0s, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=400, max_nodes=4)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 12, 128 ** -0.25)
+    gb.preload_gpu(gpu, wl, 12, 128 ** -0.25)
+    ops = [(0, MARK_OPEN, 0, 0), (0, MARK_SUB_BEGIN, 0, 40), (0, MARK_SUB_END, 0, 77),      # 4623 tokens move up
+           (1, MARK_OPEN, 0, 0), (1, MARK_SUB_BEGIN, 0, 0), (1, MARK_SUB_END, 0, 37),       # from the first token on
+           (2, MARK_OPEN, 0, 0), (2, MARK_SUB_BEGIN, 0, 500), (2, MARK_SUB_END, 0, 517)]    # 483 tokens, ragged tile
+    ora.mark(ops); gpu.mark(ops)
+    ev = ora.prune_plan([0, 1, 2]); ora.kv_compact(ev, 0, 1); ora.commit(ev)
+    pl = gpu.prune_plan([0, 1, 2]); gpu.kv_compact(pl, 0, 1); gpu.commit(pl)
+    assert ev.ok
+    check_plan(ev, gpu.plan_view())
+    ext = [sp.plan.n_kept - sp.plan.first_pruned for sp in ev.seqs]
+    assert ext == [4623, 53, 483]
+    total = sum(ext)
+    q = tensors.bits(tensors.normal_bf16(13, (0,), (total, 8, 128), 128 ** -0.25))
+    rows = sorted(set([0, 1, 7, 8, 31, 32, 33, 1000, 2007, 2008, 2040, 2041, 2100, 4055, 4056, 4100, 4600, 4621, 4622] +
+                      list(range(ext[0], total))))                                      # all rows of sequences 1 and 2
+    kv = [tuple(bf16.to_f64(x) for x in ora.gather_kv(0, b)) for b in range(3)]
+    starts = np.cumsum([0] + ext)
+    for scale in (128 ** -0.5, 0.0, -0.07):
+        got = gpu.extend_attn(0, pl, q, scale)
+        got16 = gpu.extend_attn(0, pl, q, scale, out_dtype=torch.bfloat16)
+        assert np.isfinite(got).all() and np.isfinite(got16).all()
+        want = np.zeros((len(rows), 8, 128), dtype=np.float32)
+        for i, r in enumerate(rows):
+            e = int(np.searchsorted(starts, r, side="right") - 1)
+            j = ev.seqs[e].plan.first_pruned + (r - int(starts[e]))
+            want[i] = attention.attend(bf16.to_f64(q[r]), kv[e][0][: j + 1], kv[e][1][: j + 1], scale)
+        check_attention(got[rows], want)
+        assert np.all(np.abs(got16[rows] - want) <= 2e-2 + 1e-2 * np.abs(want))
+    assert gpu.status() == 0
+
+
 @pytest.mark.parametrize("page_size", [16, 1])
 @pytest.mark.parametrize("threshold,cadence,spec_name", [(0, 4, "tiny"), (2, 9, "tiny"), (1, 16, "c1")])
 def test_in_forward_masked_variant(gb, threshold, cadence, spec_name, page_size):
