@@ -167,9 +167,9 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
       const int64_t tile = ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
       uint4 kk[4], vv[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) kk[j] = kpool[tile + j * 64 + lane];
+      for (int j = 0; j < 4; ++j) kk[j] = tim_load_stream(kpool + tile + j * 64 + lane);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) vv[j] = vpool[tile + j * 64 + lane];
+      for (int j = 0; j < 4; ++j) vv[j] = tim_load_stream(vpool + tile + j * 64 + lane);
       const int left = n - pg * TIM_PS;  // rows of this page that exist (>= 1)
 
       float s[TIM_G][4];
@@ -266,7 +266,7 @@ __device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __bui
 #define AT_LAZY_MAX 8.0f
 
 template <bool OUT_BF16, bool MASKED, bool PS1>
-__global__ void __launch_bounds__(AT_THREADS)
+__global__ void __launch_bounds__(AT_THREADS, 3)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
                              void *__restrict__ out, float scale_log2, int cpb, const uint4 *__restrict__ k_new,
                              const uint4 *__restrict__ v_new) {
@@ -277,6 +277,17 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   // blockIdx.x = sequence * kv_heads + kv head: consecutive workgroup ids go to consecutive
   // XCDs, so every XCD gets the same share of every sequence however unequal the lengths
   const int slot = blockIdx.y, kvh = blockIdx.x % cfg.kv_heads, b = blockIdx.x / cfg.kv_heads, slots = gridDim.y;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+  // Page ids run one chunk ahead of the tiles they name, so that no tile load waits for a page-id load
+  // first; the ids of the slot's first chunk are requested here, before the sequence length is known.
+  // lane i of the result holds page chunk * 16 + w * 4 + i % 4.  Entries past the sequence's end are
+  // read (the index is clamped to the table's row) but never used.
+  const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
+  auto load_pids = [&](int chunk_) {
+    return ptab[min(chunk_ * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE + (lane & (AT_PAGES_PER_WAVE - 1)), cfg.max_pages_per_seq - 1)];
+  };
+  int next_pid = 0;
+  if (!PS1) next_pid = load_pids(slot);
   const int n = st.seq_len[b];
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
@@ -286,7 +297,6 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     if (n <= 0 && slot == 0) at_empty_out<OUT_BF16>(cfg, out, b, kvh);
     return;
   }
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
 
   // B operand of the score product: Q^T, head j (zero for j >= 4), dims 32s + 8g .. +8
   uint4 qb[4];
@@ -304,16 +314,15 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
 
   const uint4 *kpool = reinterpret_cast<const uint4 *>(st.k_pool);
   const uint4 *vpool = reinterpret_cast<const uint4 *>(st.v_pool);
-  const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
   for (int chunk = slot; chunk < nchunks; chunk += used) {
     const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
     const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
-    // the wave's page ids of this chunk in one load: lane i holds page pg0 + i.  (With page
-    // size 1 a "page" below is a run of 16 tokens and every row has its own page id.)
-    int my_pid = 0;
-    if (!PS1) my_pid = ptab[min(pg0 + (lane & (AT_PAGES_PER_WAVE - 1)), max(n_pages - 1, 0))];
+    // the wave's page ids of this chunk: lane i holds page pg0 + i % 4; the next chunk's are requested now.
+    // (With page size 1 a "page" below is a run of 16 tokens and every row has its own page id.)
+    const int my_pid = next_pid;
+    if (!PS1) next_pid = load_pids(chunk + used);
     for (int pg = pg0; pg < pg1; pg += 2) {
       const bool has_b = pg + 1 < pg1;
       // in-forward variant: visibility of the pair's 32 tokens (pairs start at even pages);
@@ -344,13 +353,13 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         }
         const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
+        for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + ra + 4 * s + g);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
+        for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + rb + 4 * s + g);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = vpool[((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j];
+        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = vpool[((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j];
+        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
       } else {
         int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
         int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
@@ -361,13 +370,13 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         const int64_t tile_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
         const int64_t tile_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka[s] = kpool[tile_a + j * 16 + 4 * s + g];
+        for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + tile_a + j * 16 + 4 * s + g);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kb[s] = kpool[tile_b + j * 16 + 4 * s + g];
+        for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + tile_b + j * 16 + 4 * s + g);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = vpool[tile_a + (4 * g + i) * 16 + j];
+        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + tile_a + (4 * g + i) * 16 + j);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = vpool[tile_b + (4 * g + i) * 16 + j];
+        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + tile_b + (4 * g + i) * 16 + j);
       }
 
       // fused append: the wave that owns the sequence's last page takes the pending token's

@@ -90,15 +90,15 @@ __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const ti
       const int64_t so = lbase + s_off + (int64_t)h * 256;
       const int64_t dof = lbase + d_off + (int64_t)h * 256;
       uint4 klo[2], khi[2], vlo[2], vhi[2];
-      klo[0] = kp[so];
-      khi[0] = kp[so + 8];
-      vlo[0] = vp[so];
-      vhi[0] = vp[so + 8];
+      klo[0] = tim_load_stream(kp + so);
+      khi[0] = tim_load_stream(kp + so + 8);
+      vlo[0] = tim_load_stream(vp + so);
+      vhi[0] = tim_load_stream(vp + so + 8);
       if (two) {
-        klo[1] = kp[so + 256];
-        khi[1] = kp[so + 256 + 8];
-        vlo[1] = vp[so + 256];
-        vhi[1] = vp[so + 256 + 8];
+        klo[1] = tim_load_stream(kp + so + 256);
+        khi[1] = tim_load_stream(kp + so + 256 + 8);
+        vlo[1] = tim_load_stream(vp + so + 256);
+        vhi[1] = tim_load_stream(vp + so + 256 + 8);
       }
       if (d != 0) {
 #pragma unroll
@@ -117,15 +117,15 @@ __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const ti
           }
         }
       }
-      kw[dof] = klo[0];
-      kw[dof + 8] = khi[0];
-      vw[dof] = vlo[0];
-      vw[dof + 8] = vhi[0];
+      tim_store_stream(kw + dof, klo[0]);
+      tim_store_stream(kw + dof + 8, khi[0]);
+      tim_store_stream(vw + dof, vlo[0]);
+      tim_store_stream(vw + dof + 8, vhi[0]);
       if (two) {
-        kw[dof + 256] = klo[1];
-        kw[dof + 256 + 8] = khi[1];
-        vw[dof + 256] = vlo[1];
-        vw[dof + 256 + 8] = vhi[1];
+        tim_store_stream(kw + dof + 256, klo[1]);
+        tim_store_stream(kw + dof + 256 + 8, khi[1]);
+        tim_store_stream(vw + dof + 256, vlo[1]);
+        tim_store_stream(vw + dof + 256 + 8, vhi[1]);
       }
     }
   }

@@ -22,7 +22,7 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   c->bound = false;
   c->n_cu = 256;
   c->attn_impl = 1;
-  c->attn_cpb = 4;
+  c->attn_cpb = 8;
   c->attn_fill = 2;
   if (const char *v = std::getenv("TIM_ATTN_FILL")) {  // tuning experiments only
     const int x = std::atoi(v);
