@@ -334,7 +334,8 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       }
       uint4 ka[4], kb[4], va[4], vb[4];
       if (PS1) {
-        // one page per token: the K operand row j and the V rows 4g+i each bring their own id
+        // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  (Ordinary
+        // loads here: a 256-byte row is touched by four load instructions, and without the L1 they were slower.)
         const int ta = pg * TIM_PS, tb = has_b ? ta + TIM_PS : ta, last = n - 1;
         int ids[10];
         ids[0] = ptab[min(ta + j, last)];
@@ -353,13 +354,13 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         }
         const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + ra + 4 * s + g);
+        for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + rb + 4 * s + g);
+        for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
+        for (int i = 0; i < 4; ++i) va[i] = vpool[((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
+        for (int i = 0; i < 4; ++i) vb[i] = vpool[((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j];
       } else {
         int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
         int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
