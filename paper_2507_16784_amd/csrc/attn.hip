@@ -68,34 +68,79 @@ __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
 // last block to finish, behind an agent-scope counter, was measured and rejected: the
 // release/acquire fences it needs write back and invalidate the XCD's whole L2 per block
 // and cost 6x the kernel's run time.)
+typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float at_f32x4 __attribute__((ext_vector_type(4)));
+typedef float at_f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t at_pack_bf16(float lo, float hi) {
+  at_f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, at_bf16x2));
+}
+__device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __builtin_bit_cast(at_bf16x8, u); }
+
+// Partials.  The few KB a block writes cost far more than their size: measured on a uniform 4.3 GB launch, the
+// kernel runs at 6.80 TB/s without them and at 6.46 TB/s with 2 KiB per block of ordinary stores into the
+// workspace (not the stores' latency: the same stores into one small hot region cost nothing; the cost is
+// proportional to the bytes that reach memory while the read stream is running).  So they are kept small and
+// written through (agent-scope stores, 6.58 TB/s): with bf16 output a slot's partial output is stored
+// normalised (o / l) in bf16, 1 KiB per block; with fp32 output unnormalised in fp32.  m and l are fp32.
+__device__ __forceinline__ void at_store_through(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void at_store_through(uint32_t *p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int NS, bool OUT_BF16>
 __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &ws, void *out, const float *red_m,
                                           const float *red_l, const float *red_o, int b, int kvh, int slot, int slots,
                                           int used) {
   const int tid = threadIdx.x;
-#pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int idx = tid + r * AT_THREADS;  // 0..511 = (h, dim)
-    const int h = idx >> 7, dim = idx & 127;
-    float mx = AT_NEG_BIG;
+  // the NS states in LDS merged for one (head, dim): returns o, sets m and l
+  auto merged = [&](int h, int dim, float &mx, float &lt) {
+    mx = AT_NEG_BIG;
 #pragma unroll
     for (int s2 = 0; s2 < NS; ++s2) mx = fmaxf(mx, red_m[s2 * TIM_G + h]);
-    float lt = 0.f, ot = 0.f;
+    float ot = 0.f;
+    lt = 0.f;
 #pragma unroll
     for (int s2 = 0; s2 < NS; ++s2) {
       const float sc = __builtin_amdgcn_exp2f(red_m[s2 * TIM_G + h] - mx);
       lt = fmaf(red_l[s2 * TIM_G + h], sc, lt);
       ot = fmaf(red_o[(s2 * TIM_G + h) * TIM_D + dim], sc, ot);
     }
-    const int hq = kvh * TIM_G + h;
+    return ot;
+  };
+  if (OUT_BF16 && used > 1) {
+    // bf16 partial: thread -> head tid / 64, dims 2 (tid % 64) and the next one, one 32-bit word
+    static_assert(AT_THREADS == TIM_G * TIM_D / 2, "one pair of dims per thread");
+    const int h = tid >> 6, d0 = 2 * (tid & 63);
+    float mx, lt, mx1, lt1;
+    const float o0 = merged(h, d0, mx, lt), o1 = merged(h, d0 + 1, mx1, lt1);
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;  // (a slot whose tokens are all hidden has l = 0)
+    const int64_t pi = ((int64_t)b * cfg.q_heads + kvh * TIM_G + h) * slots + slot;
+    at_store_through(reinterpret_cast<uint32_t *>(ws.o) + (pi * TIM_D + d0) / 2, at_pack_bf16(o0 * inv, o1 * inv));
+    if (d0 == 0) {
+      at_store_through(ws.ml + pi * 2, mx);
+      at_store_through(ws.ml + pi * 2 + 1, lt);
+    }
+    return;
+  }
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int idx = tid + r * AT_THREADS;  // 0..511 = (h, dim)
+    const int h = idx >> 7, dim = idx & 127, hq = kvh * TIM_G + h;
+    float mx, lt;
+    const float ot = merged(h, dim, mx, lt);
     if (used == 1) {
       at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, ot / lt);
     } else {
       const int64_t pi = ((int64_t)b * cfg.q_heads + hq) * slots + slot;
-      ws.o[pi * TIM_D + dim] = ot;
+      at_store_through(ws.o + pi * TIM_D + dim, ot);
       if (dim == 0) {
-        ws.ml[pi * 2] = mx;
-        ws.ml[pi * 2 + 1] = lt;
+        at_store_through(ws.ml + pi * 2, mx);
+        at_store_through(ws.ml + pi * 2 + 1, lt);
       }
     }
   }
@@ -252,16 +297,6 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
 // renews it (cross-lane max, rescale of the accumulators) when a score exceeds it by more
 // than 2^8; until then p = exp2(t - ref) <= 256 is exact enough in bf16/fp32.  The row
 // sums stay per lane and are added once at the end.
-typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
-typedef float at_f32x4 __attribute__((ext_vector_type(4)));
-typedef float at_f32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ uint32_t at_pack_bf16(float lo, float hi) {
-  at_f32x2 f = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, at_bf16x2));
-}
-__device__ __forceinline__ at_bf16x8 at_as_bf16x8(const uint4 &u) { return __builtin_bit_cast(at_bf16x8, u); }
 
 #define AT_LAZY_MAX 8.0f
 
@@ -553,22 +588,34 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
   __syncthreads();
   const float mx = fmaxf(red[0], red[1]);
   const float w = tid < used ? __builtin_amdgcn_exp2f(m - mx) : 0.f;
-  wgt[tid] = w;
+  wgt[tid] = OUT_BF16 ? w * l : w;  // a bf16 partial is stored normalised: its weight carries l
   const float ws_l = at_wave_sum(w * l);
   if ((tid & 63) == 0) red[2 + (tid >> 6)] = ws_l;
   __syncthreads();
   const float lt = red[2] + red[3];
-  const float *o = ws.o + p0 * TIM_D + tid;
   float acc = 0.f;
   int s = 0;
-  for (; s + 8 <= used; s += 8) {
-    float v[8];
+  if (OUT_BF16) {
+    const uint16_t *o = reinterpret_cast<const uint16_t *>(ws.o) + p0 * TIM_D + tid;
+    for (; s + 8 <= used; s += 8) {
+      uint16_t v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
+      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc = fmaf(v[u], wgt[s + u], acc);
+      for (int u = 0; u < 8; ++u) acc = fmaf(__uint_as_float((uint32_t)v[u] << 16), wgt[s + u], acc);
+    }
+    for (; s < used; ++s) acc = fmaf(__uint_as_float((uint32_t)o[(int64_t)s * TIM_D] << 16), wgt[s], acc);
+  } else {
+    const float *o = ws.o + p0 * TIM_D + tid;
+    for (; s + 8 <= used; s += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc = fmaf(v[u], wgt[s + u], acc);
+    }
+    for (; s < used; ++s) acc = fmaf(o[(int64_t)s * TIM_D], wgt[s], acc);
   }
-  for (; s < used; ++s) acc = fmaf(o[(int64_t)s * TIM_D], wgt[s], acc);
   at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, acc / lt);
 }
 
