@@ -74,6 +74,7 @@ def test_config3_full_size_sampled():
     g.manual_seed(5)
     rnd = lambda *s: torch.randn(*s, generator=g, device="cuda").to(torch.bfloat16)
     out = torch.empty(64, 32, 128, dtype=torch.float32, device="cuda")
+    out16 = torch.empty(64, 32, 128, dtype=torch.bfloat16, device="cuda")      # bench.py's output type
     sample_layers = [0, 17, 35]
     big = {0: 0, 4: 1, 8: 2}                                   # step -> sequence taking its big flush
     okv = {}                                                   # (layer, flushed sequence) -> oracle-side [K, V] bits
@@ -117,6 +118,8 @@ def test_config3_full_size_sampled():
             q, kn, vn = rnd(64, 32, 128), rnd(64, 8, 128), rnd(64, 8, 128)
             ctx.tim_decode_attn_append(layer, q, kn, vn, out, shape.q_scale, hint)     # as bench.py launches it
             got = out.cpu().numpy()
+            ctx.tim_decode_attn(layer, q, out16, shape.q_scale, hint)                  # same state, bf16 output (bf16 partials)
+            got16 = out16.float().cpu().numpy()
             kn_b, vn_b = tensors.bits(kn.cpu()), tensors.bits(vn.cpu())
             for (l, b), kv in okv.items():                                             # the oracle's caches grow too
                 if l == layer:
@@ -132,6 +135,7 @@ def test_config3_full_size_sampled():
                     kb, vb = ko, vo
                 want = attend(bf16.to_f64(tensors.bits(q[b].cpu())), bf16.to_f64(kb), bf16.to_f64(vb), shape.q_scale)
                 check_attention(got[b], want.astype(np.float32))
+                assert np.all(np.abs(got16[b] - want) <= 2e-2 + 1e-2 * np.abs(want))
         assert ctx.tim_status() == 0
     del ctx, plan
     gc.collect()
