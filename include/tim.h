@@ -269,7 +269,10 @@ int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream stream);
  * [max_batch][q_heads][128], rotated at position seq_len-1.  out: device
  * [max_batch][q_heads][128] in out_dtype.  max_seq_len: an upper bound on the
  * batch's lengths used only to size the launch (0 = assume full tables); longer
- * sequences are still handled in full.  Uses tim_state.attn_ws.
+ * sequences are still handled in full.  Uses tim_state.attn_ws: a long sequence
+ * is split over several blocks whose partial results pass through it, in fp32
+ * when out_dtype is fp32 and as bf16 (normalised, with fp32 maximum and sum)
+ * when it is bf16.
  */
 int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                     int32_t max_seq_len, tim_stream stream);
