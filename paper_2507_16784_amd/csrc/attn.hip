@@ -62,12 +62,6 @@ __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
 }
 
 
-// Block epilogue shared by both variants.  The NS (m, l, o) states the block holds in LDS
-// are merged (log-sum-exp algebra).  If the block is the sequence's only one, the result is
-// final; otherwise it becomes this slot's partial for the merge kernel.  (Merging in the
-// last block to finish, behind an agent-scope counter, was measured and rejected: the
-// release/acquire fences it needs write back and invalidate the XCD's whole L2 per block
-// and cost 6x the kernel's run time.)
 typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float at_f32x4 __attribute__((ext_vector_type(4)));
@@ -92,6 +86,12 @@ __device__ __forceinline__ void at_store_through(uint32_t *p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Block epilogue shared by both variants.  The NS (m, l, o) states the block holds in LDS
+// are merged (log-sum-exp algebra).  If the block is the sequence's only one, the result is
+// final; otherwise it becomes this slot's partial for the merge kernel.  (Merging in the
+// last block to finish, behind an agent-scope counter, was measured and rejected: the
+// release/acquire fences it needs write back and invalidate the XCD's whole L2 per block
+// and cost 6x the kernel's run time.)
 template <int NS, bool OUT_BF16>
 __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &ws, void *out, const float *red_m,
                                           const float *red_l, const float *red_o, int b, int kvh, int slot, int slots,
