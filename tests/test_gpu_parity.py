@@ -230,6 +230,35 @@ def test_config4_prune_heavy_recycling(gb):
     assert ora.seq_len.max() < p0
 
 
+@pytest.mark.parametrize("case", range(10))
+def test_seeded_shape_sweep(gb, case):
+    """Shapes no other test fixes by hand: head counts that are not powers of two, layer counts
+    that are not multiples of the compaction kernel's layer group, odd batches, both page sizes,
+    both rotary bases, tight and roomy page tables, fused and separate append - drawn from a seed."""
+    rng = np.random.RandomState(1000 + case)
+    kv_heads = int(rng.choice([1, 2, 3, 5, 8]))
+    layers = int(rng.choice([1, 2, 3, 5]))
+    batch = int(rng.randint(1, 7))
+    page_size = 1 if case % 3 == 2 else 16
+    threshold = int(rng.randint(0, 4))
+    cadence = int(rng.randint(1, 13))
+    steps = int(rng.randint(20, 41))
+    p0s = [int(x) for x in rng.randint(6, 900, size=batch)]
+    spec = SPEC_TINY if rng.randint(2) else SPEC_C1
+    traces = [generate(2000 + 17 * case + b, p + steps + 1, spec) for b, p in enumerate(p0s)]
+    wl = Workload(traces, p0s, steps, every(cadence, steps, batch, first=int(rng.randint(0, cadence))))
+    longest = max(p0s) + steps
+    tight = (longest + page_size - 1) // page_size
+    cfg = harness.make_config(wl, layers=layers, q_heads=4 * kv_heads, kv_heads=kv_heads,
+                              headroom_pages=int(rng.randint(4, 40)) * (16 // page_size) * batch, page_size=page_size,
+                              max_pages_per_seq=tight if rng.randint(2) else tight + int(rng.randint(1, 40)),
+                              rope_base=float(rng.choice([1.0e4, 1.0e6])))
+    kv_scale = float(rng.choice([1.0, 128 ** -0.5]))
+    sm_scale = float(rng.choice([128 ** -0.5, 0.02, 0.3]))
+    replay(gb, wl, cfg, threshold, 3000 + case, kv_scale, sm_scale, attend_every=int(rng.randint(1, 4)),
+           fused=bool(rng.randint(2)))
+
+
 @pytest.mark.parametrize("n", [1, 15, 16, 17, 255, 256, 257, 1031])
 def test_attention_lengths_and_needle(gb, n):
     """No tree at all: plain paged decode attention at page-aligned and ragged lengths,
