@@ -444,6 +444,47 @@ def test_extend_attention_long_context_and_scales(gb):
     assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("case", range(6))
+def test_extend_attention_seeded_boundaries(gb, case):
+    """Extend attention with the first pruned token and the number of moved tokens placed on, just before
+    and just after page, page-pair, wave (8 tokens) and tile (32 tokens) boundaries, for head counts that
+    are not powers of two; every row against the oracle."""
+    from paper_2507_16784_amd.workload import tensors
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    rng = np.random.RandomState(500 + case)
+    kv_heads = int(rng.choice([1, 2, 3, 5, 8]))
+    nseq = 4
+    firsts = [int(x) for x in rng.choice([0, 1, 15, 16, 17, 31, 32, 33, 47, 48, 63, 64, 65, 200, 333], size=nseq)]
+    gaps = [int(x) for x in rng.choice([1, 2, 16, 17, 40], size=nseq)]                # pruned tokens
+    moved = [int(x) for x in rng.choice([1, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 97, 130], size=nseq)]
+    p0s = [f + g + m for f, g, m in zip(firsts, gaps, moved)]
+    tr = Trace(max(p0s) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * nseq, p0s, 1, {})
+    cfg = harness.make_config(wl, layers=2, q_heads=4 * kv_heads, kv_heads=kv_heads, headroom_pages=80, max_nodes=4)
+    ora = OracleRuntime(cfg, 0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 40 + case, 128 ** -0.25)
+    gb.preload_gpu(gpu, wl, 40 + case, 128 ** -0.25)
+    ops = []
+    for b in range(nseq):
+        ops += [(b, MARK_OPEN, 0, 0), (b, MARK_SUB_BEGIN, 0, firsts[b]), (b, MARK_SUB_END, 0, firsts[b] + gaps[b])]
+    ora.mark(ops); gpu.mark(ops)
+    ids = list(range(nseq))
+    ev = ora.prune_plan(ids); ora.kv_compact(ev, 0, 2); ora.commit(ev)
+    pl = gpu.prune_plan(ids); gpu.kv_compact(pl, 0, 2); gpu.commit(pl)
+    assert ev.ok
+    check_plan(ev, gpu.plan_view())
+    assert [sp.plan.n_kept - sp.plan.first_pruned for sp in ev.seqs] == moved
+    assert [sp.plan.first_pruned for sp in ev.seqs] == firsts
+    q = tensors.bits(tensors.normal_bf16(50 + case, (0,), (sum(moved), 4 * kv_heads, 128), 128 ** -0.25))
+    for layer in (0, 1):
+        want = ora.extend_attn(layer, ev, q, 128 ** -0.5)
+        check_attention(gpu.extend_attn(layer, pl, q, 128 ** -0.5), want)
+        got16 = gpu.extend_attn(layer, pl, q, 128 ** -0.5, out_dtype=torch.bfloat16)
+        assert np.all(np.abs(got16 - want) <= 2e-2 + 1e-2 * np.abs(want))
+    assert gpu.status() == 0
+
+
 @pytest.mark.parametrize("page_size", [16, 1])
 @pytest.mark.parametrize("threshold,cadence,spec_name", [(0, 4, "tiny"), (2, 9, "tiny"), (1, 16, "c1")])
 def test_in_forward_masked_variant(gb, threshold, cadence, spec_name, page_size):
