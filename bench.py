@@ -86,6 +86,8 @@ def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, pag
     return ctx, L
 
 
+SCHEDULE = True          # call tim_attn_schedule once per decode step (--no-schedule turns it off for A/B runs)
+
 INT_STATE = ("page_table", "seq_len", "free_stack", "free_top", "status", "node_tok_begin", "node_sub_begin",
              "node_sub_end", "node_tok_end", "node_list_order", "n_nodes", "lists_done", "keep_mask")
 
@@ -124,6 +126,8 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
             _, s0, host = pending.pop(0)
             hint_len, hint_step = int(host.max()), s0
         hint = hint_len + (step - hint_step) + 1
+        if SCHEDULE:                                 # once per step: the layers' launches take only the slots in use
+            ctx.tim_attn_schedule(hint)
         for layer in range(layers_run):
             la = layer % L_alloc
             if flush_kind == "mask":
@@ -298,6 +302,8 @@ def horizon_mode(torch, tim, np, configs, args):
             ctx.tim_plan_commit(plan)
         ctx.tim_seq_advance()
         if full:
+            if SCHEDULE:
+                ctx.tim_attn_schedule(32768)
             for layer in range(shape.layers):
                 ctx.tim_decode_attn_append(layer, q[layer], kn[layer], vn[layer], out, shape.q_scale, 32768)
         return len(ids)
@@ -395,6 +401,7 @@ def main():
     ap.add_argument("--layers-alloc", type=int, default=0, help="debug: allocate fewer layer pools and alias them")
     ap.add_argument("--seed", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-schedule", action="store_true", help="A/B: leave out the per-step tim_attn_schedule call")
     ap.add_argument("--dump", default="", help="write per-step lengths and attention timings to this .npz")
     ap.add_argument("--mode", default="window", choices=["window", "flush", "sweep"],
                     help="window: the decode window (default, the headline number); flush: all big flushes in one "
@@ -411,6 +418,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
+    global SCHEDULE
+    SCHEDULE = not args.no_schedule
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no cross-GPU exchange and every box here has one GPU; "
               "run with --gpus 1", file=sys.stderr)
@@ -490,6 +499,8 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             ctx.tim_seq_advance()
+            if SCHEDULE:
+                ctx.tim_attn_schedule(full_len)
             for layer in range(shape.layers):
                 la = layer % L_alloc
                 ctx.tim_decode_attn_append(la, staged["q"][layer], staged["k_new"][layer], staged["v_new"][layer],

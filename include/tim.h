@@ -278,6 +278,23 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
                     int32_t max_seq_len, tim_stream stream);
 
 /*
+ * Optional, once per decode step after the lengths are final (after tim_seq_advance and any
+ * flush): lists, in tim_state.attn_ws, the blocks the step's attention launches need - only
+ * the slots each sequence really uses, longest sequence first - so that all decode-attention
+ * calls up to the next change of a length launch exactly that work in that order.  The
+ * split-K decomposition of Sec. 3.1's paged attention is otherwise sized for the longest
+ * sequence, and a batch of very unequal lengths (working memories before and after their
+ * flush) spends a good part of a launch on blocks that find nothing to do.  max_seq_len as
+ * in tim_decode_attn; the calls that follow use this call's bound and ignore their own.
+ * The schedule lapses at the next tim_seq_advance, tim_seq_extend, tim_plan_commit,
+ * tim_pool_reset or tim_bind.  A caller that changes tim_state.seq_len by other means must
+ * call this again: a stale schedule is detected per block and reported as
+ * TIM_ERR_INVALID_ARG in the status word (outputs are then undefined, accesses stay in
+ * bounds).  Results are those of the unscheduled calls up to summation order.
+ */
+int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream);
+
+/*
  * tim_kv_append and tim_decode_attn of one layer in a single launch: the wave that reads a
  * sequence's last page takes the pending token's row from k_new / v_new (same layout as in
  * tim_kv_append), uses it, and stores it into the pool.  Results are those of the two calls.

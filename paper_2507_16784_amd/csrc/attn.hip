@@ -48,9 +48,11 @@ __device__ __forceinline__ void at_unpack(const uint4 &u, float (&f)[8]) {
 }
 
 struct AttnWs {
-  float *ml;  // [B][Hq][slots][2]
-  float *o;   // [B][Hq][slots][128]
+  float *ml;             // [B][Hq][slots][2]
+  float *o;              // [B][Hq][slots][128]
+  const int32_t *sched;  // work list written by tim_attn_schedule, or nullptr (see at_take_work)
 };
+#define AT_SCHED_HDR 4  // words before the items: [0] = number of items; an item is {sequence, slot, length, slots used}
 
 template <bool OUT_BF16>
 __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
@@ -153,27 +155,83 @@ __device__ __forceinline__ void at_empty_out(const tim_config &cfg, void *out, i
     at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + kvh * TIM_G) * TIM_D + idx, 0.f);
 }
 
+// Slots a sequence of n tokens occupies: one per `cpb` chunks, at most `slots`.
+__device__ __forceinline__ int at_slots_used(int n, int cpb, int slots) {
+  const int n_pages = (n + TIM_PS - 1) / TIM_PS;
+  const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
+  return min(slots, (nchunks + cpb - 1) / cpb);
+}
+
+// Which (sequence, kv head, slot) this workgroup takes; false = none (uniform for the block).
+//
+// Without a schedule the grid is (batch * kv_heads, slots) with `slots` sized for the host's bound on the
+// longest sequence: consecutive workgroup ids run over (sequence, kv head) first and are dealt round-robin
+// to the 8 XCDs, so every XCD gets the same share of every sequence (with 8 kv heads: one head per XCD).
+// Slots beyond a sequence's need exit at once.  That is fine for batches of similar lengths.  Next to
+// one 32K-token sequence, 63 sequences of 2.5K tokens leave 14 of 16 slots idle, and the long sequence's
+// last slots are the last workgroups of the grid, behind all the idle ones: measured 161 us for a launch
+// whose bytes take 117 us.
+//
+// With a schedule (tim_attn_schedule: one small kernel per decode step, after the lengths are final) the
+// grid is one-dimensional and workgroup i takes kv head i % kv_heads of item i / kv_heads of a list that
+// holds only the slots in use, longest sequence first.  Workgroups beyond the list retire after two scalar
+// loads, at the end of the grid, while the last busy ones still run.
+struct AtWork {
+  int b, kvh, slot, n, used;
+  int n_live;  // the sequence's length as it is now: differs from n only under a stale schedule
+};
+template <bool OUT_BF16>
+__device__ __forceinline__ bool at_take_work(const tim_config &cfg, const tim_state &st, const AttnWs &ws, void *out,
+                                             int slots, int cpb, AtWork &wk) {
+  // Everything here is wave-uniform and must stay on the scalar path: a vector load issued by a new
+  // workgroup queues behind the tile loads its CU already has in flight (measured: 2.5 us more per idle
+  // workgroup).  Hence no store or atomic before the last of these loads - the compiler would then no
+  // longer trust the scalar cache - and the stale-schedule report is left to the caller (at_check_live).
+  wk.kvh = blockIdx.x % cfg.kv_heads;
+  if (ws.sched != nullptr) {
+    const int item = blockIdx.x / cfg.kv_heads;  // below batch * slots, the list's capacity
+    const int total = ws.sched[0];
+    const int4 e = reinterpret_cast<const int4 *>(ws.sched + AT_SCHED_HDR)[item];
+    if (item >= total) return false;
+    wk.b = e.x;
+    wk.slot = e.y;
+    wk.n = e.z;
+    wk.used = e.w;
+    wk.n_live = st.seq_len[wk.b];
+  } else {
+    wk.b = blockIdx.x / cfg.kv_heads;
+    wk.slot = blockIdx.y;
+    wk.n = wk.n_live = st.seq_len[wk.b];
+    wk.used = at_slots_used(wk.n, cpb, slots);
+    if (wk.slot >= max(wk.used, 1)) return false;
+  }
+  if (wk.n <= 0) {  // a sequence without tokens has one workgroup per kv head, which defines its output as zero
+    at_empty_out<OUT_BF16>(cfg, out, wk.b, wk.kvh);
+    return false;
+  }
+  return true;
+}
+// A length that changed since the schedule was written is reported; the stale one stays in use (every page
+// id is checked before it is dereferenced, so the worst outcome is a wrong output).
+__device__ __forceinline__ void at_check_live(const tim_state &st, const AtWork &wk) {
+  if (wk.n_live != wk.n) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+}
+
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(AT_THREADS)
 tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
-                        void *__restrict__ out, float scale_log2, int cpb, const uint4 *__restrict__,
+                        void *__restrict__ out, float scale_log2, int cpb, int slots, const uint4 *__restrict__,
                         const uint4 *__restrict__) {
   __shared__ float red_m[AT_WAVES * 4][TIM_G];
   __shared__ float red_l[AT_WAVES * 4][TIM_G];
   __shared__ float red_o[AT_WAVES * 4][TIM_G][TIM_D];
 
-  // blockIdx.x = sequence * kv_heads + kv head: consecutive workgroup ids go to consecutive
-  // XCDs, so every XCD gets the same share of every sequence however unequal the lengths
-  const int slot = blockIdx.y, kvh = blockIdx.x % cfg.kv_heads, b = blockIdx.x / cfg.kv_heads, slots = gridDim.y;
-  const int n = st.seq_len[b];
+  AtWork wk;
+  if (!at_take_work<OUT_BF16>(cfg, st, ws, out, slots, cpb, wk)) return;
+  at_check_live(st, wk);
+  const int b = wk.b, kvh = wk.kvh, slot = wk.slot, n = wk.n, used = wk.used;
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
-  const int used = min(slots, (nchunks + cpb - 1) / cpb);
-  if (slot >= used) {  // uniform for the block
-    if (n <= 0 && slot == 0) at_empty_out<OUT_BF16>(cfg, out, b, kvh);
-    return;
-  }
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
 
   // the group's four query rows, dims 8c..8c+7, pre-scaled so that exp2 gives softmax
@@ -303,35 +361,28 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
 template <bool OUT_BF16, bool MASKED, bool PS1>
 __global__ void __launch_bounds__(AT_THREADS, 3)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
-                             void *__restrict__ out, float scale_log2, int cpb, const uint4 *__restrict__ k_new,
-                             const uint4 *__restrict__ v_new) {
+                             void *__restrict__ out, float scale_log2, int cpb, int slots,
+                             const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new) {
   __shared__ float red_m[AT_WAVES][TIM_G];
   __shared__ float red_l[AT_WAVES][TIM_G];
   __shared__ float red_o[AT_WAVES][TIM_G][TIM_D];
 
-  // blockIdx.x = sequence * kv_heads + kv head: consecutive workgroup ids go to consecutive
-  // XCDs, so every XCD gets the same share of every sequence however unequal the lengths
-  const int slot = blockIdx.y, kvh = blockIdx.x % cfg.kv_heads, b = blockIdx.x / cfg.kv_heads, slots = gridDim.y;
+  AtWork wk;
+  if (!at_take_work<OUT_BF16>(cfg, st, ws, out, slots, cpb, wk)) return;
+  const int b = wk.b, kvh = wk.kvh, slot = wk.slot, n = wk.n, used = wk.used;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
   // Page ids run one chunk ahead of the tiles they name, so that no tile load waits for a page-id load
-  // first; the ids of the slot's first chunk are requested here, before the sequence length is known.
-  // lane i of the result holds page chunk * 16 + w * 4 + i % 4.  Entries past the sequence's end are
-  // read (the index is clamped to the table's row) but never used.
+  // first.  lane i of the result holds page chunk * 16 + w * 4 + i % 4.  Entries past the sequence's
+  // end are read (the index is clamped to the table's row) but never used.
   const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
   auto load_pids = [&](int chunk_) {
     return ptab[min(chunk_ * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE + (lane & (AT_PAGES_PER_WAVE - 1)), cfg.max_pages_per_seq - 1)];
   };
   int next_pid = 0;
   if (!PS1) next_pid = load_pids(slot);
-  const int n = st.seq_len[b];
+  at_check_live(st, wk);
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  // a sequence occupies one slot per `cpb` chunks (at most `slots`); the rest exit at once
-  const int used = min(slots, (nchunks + cpb - 1) / cpb);
-  if (slot >= used) {  // uniform for the block
-    if (n <= 0 && slot == 0) at_empty_out<OUT_BF16>(cfg, out, b, kvh);
-    return;
-  }
 
   // B operand of the score product: Q^T, head j (zero for j >= 4), dims 32s + 8g .. +8
   uint4 qb[4];
@@ -619,14 +670,69 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
   at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, acc / lt);
 }
 
+// words of the workspace that hold the partials; the schedule follows them
+static int64_t at_partials_words(const tim_config &cfg) {
+  return (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * (TIM_D + 2);
+}
+
 extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
   if (!cfg) return 0;
-  return (int64_t)cfg->max_batch * cfg->q_heads * AT_MAX_SLOTS * (TIM_D + 2) * (int64_t)sizeof(float);
+  return at_partials_words(*cfg) * (int64_t)sizeof(float) +
+         (AT_SCHED_HDR + 4 * (int64_t)cfg->max_batch * AT_MAX_SLOTS) * (int64_t)sizeof(int32_t);
+}
+
+// Launch shape for a bound on the longest sequence: chunks per block and slots.
+static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int *slots_out) {
+  const tim_config &cfg = ctx->cfg;
+  const int full = cfg.max_pages_per_seq * cfg.page_size;
+  const int bound = (max_seq_len == 0 || max_seq_len > full) ? full : max_seq_len;
+  const int max_pages = (bound + TIM_PS - 1) / TIM_PS;
+  const int nchunks = (max_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
+  const int rows = cfg.max_batch * cfg.kv_heads;
+  // chunks per block: as many as still leave enough blocks to fill the chip several times
+  int cpb = ctx->attn_cpb;
+  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < ctx->attn_fill * (int64_t)ctx->n_cu) --cpb;
+  int slots = (nchunks + cpb - 1) / cpb;
+  if (slots > AT_MAX_SLOTS) slots = AT_MAX_SLOTS;
+  if (slots < 1) slots = 1;
+  *cpb_out = cpb;
+  *slots_out = slots;
+}
+
+// The work list of at_take_work: thread b places the items of sequence b behind those of every longer
+// sequence (ties: lower index first).  Quadratic in the batch, which is a few thousand at most.
+__global__ void __launch_bounds__(256)
+tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sched, int slots, int cpb) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= cfg.max_batch) return;
+  const int n = st.seq_len[b];
+  const int used = at_slots_used(n, cpb, slots);
+  int before = 0, total = 0;
+  for (int o = 0; o < cfg.max_batch; ++o) {
+    const int no = st.seq_len[o];
+    const int items = max(at_slots_used(no, cpb, slots), 1);
+    total += items;
+    if (no > n || (no == n && o < b)) before += items;
+  }
+  if (b == 0) sched[0] = total;
+  int4 *items = reinterpret_cast<int4 *>(sched + AT_SCHED_HDR);
+  for (int s2 = 0; s2 < max(used, 1); ++s2) items[before + s2] = make_int4(b, s2, n, used);
+}
+
+extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream) {
+  if (!ctx || !ctx->bound || max_seq_len < 0) return TIM_ERR_INVALID_ARG;
+  at_shape(ctx, max_seq_len, &ctx->sched_cpb, &ctx->sched_slots);
+  int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
+  hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3((ctx->cfg.max_batch + 255) / 256), dim3(256), 0, tim_hs(stream),
+                     ctx->cfg, ctx->st, sched, ctx->sched_slots, ctx->sched_cpb);
+  TIM_LAUNCH_CHECK();
+  ctx->sched_valid = true;
+  return TIM_OK;
 }
 
 template <int IMPL, bool OUT_BF16>  // 0 = vector ALU, 1 = matrix cores, 2 = matrix cores with visibility mask
 static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
-                      float scale_log2, int cpb, const void *k_new, const void *v_new) {
+                      float scale_log2, int cpb, int slots, const void *k_new, const void *v_new) {
   const bool ps1 = ctx->cfg.page_size == 1;
   auto kernel = IMPL == 2   ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, true, true> : tim_attn_partial_mfma_kernel<OUT_BF16, true, false>)
                 : IMPL == 1 ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false, true> : tim_attn_partial_mfma_kernel<OUT_BF16, false, false>)
@@ -637,10 +743,10 @@ static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, 
     // events attached to the dispatch itself: the kernel's own begin/end, no extra barrier
     const int i = ctx->timing_n++;
     hipExtLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->ev_start[i], ctx->ev_stop[i], 0, ctx->cfg, ctx->st,
-                          ws, layer, q4, out, scale_log2, cpb, kn, vn);
+                          ws, layer, q4, out, scale_log2, cpb, slots, kn, vn);
   } else {
-    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb, kn,
-                       vn);
+    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb,
+                       slots, kn, vn);
   }
 }
 
@@ -685,33 +791,33 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
       (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
     return TIM_ERR_INVALID_ARG;
   const tim_config &cfg = ctx->cfg;
-  const int full = cfg.max_pages_per_seq * cfg.page_size;
-  const int bound = (max_seq_len == 0 || max_seq_len > full) ? full : max_seq_len;
-  const int max_pages = (bound + TIM_PS - 1) / TIM_PS;
-  const int nchunks = (max_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  const int rows = cfg.max_batch * cfg.kv_heads;
-  // chunks per block: as many as still leave enough blocks to fill the chip several times
-  int cpb = ctx->attn_cpb;
-  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < ctx->attn_fill * (int64_t)ctx->n_cu) --cpb;
-  int slots = (nchunks + cpb - 1) / cpb;
-  if (slots > AT_MAX_SLOTS) slots = AT_MAX_SLOTS;
-  if (slots < 1) slots = 1;
+  int cpb, slots;
   AttnWs ws;
   ws.ml = ctx->st.attn_ws;
   ws.o = ws.ml + (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * 2;
+  ws.sched = nullptr;
+  dim3 grid;
+  if (ctx->sched_valid) {  // the schedule's shape, not this call's bound: the merge must see the same slots
+    cpb = ctx->sched_cpb;
+    slots = ctx->sched_slots;
+    ws.sched = reinterpret_cast<const int32_t *>(ctx->st.attn_ws + at_partials_words(cfg));
+    grid = dim3(cfg.max_batch * cfg.kv_heads * slots);  // an upper bound on the list's length
+  } else {
+    at_shape(ctx, max_seq_len, &cpb, &slots);
+    grid = dim3(cfg.max_batch * cfg.kv_heads, slots);
+  }
   const float scale_log2 = sm_scale * 1.4426950408889634f;
   hipStream_t s = tim_hs(stream);
-  dim3 grid(cfg.max_batch * cfg.kv_heads, slots);
   const bool bf = out_dtype == TIM_OUT_BF16;
   if (masked) {
-    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
-    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
   } else if (ctx->attn_impl == 1) {
-    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
-    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
   } else {
-    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
-    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, k_new, v_new);
+    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
   }
   TIM_LAUNCH_CHECK();
   if (slots > 1) {  // with one slot every block has already written its final output

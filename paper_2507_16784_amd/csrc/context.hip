@@ -57,5 +57,6 @@ extern "C" int tim_bind(tim_ctx *ctx, const tim_state *s) {
   if (s->attn_ws_bytes < tim_attn_ws_bytes(&ctx->cfg)) return TIM_ERR_INVALID_ARG;
   ctx->st = *s;
   ctx->bound = true;
+  ctx->sched_valid = false;
   return TIM_OK;
 }

@@ -373,6 +373,7 @@ extern "C" int tim_prune_plan(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_se
 
 extern "C" int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream stream) {
   if (!plan_ok(ctx, plan) || plan->n_seqs <= 0 || plan->n_seqs > plan->max_seqs) return TIM_ERR_INVALID_ARG;
+  ctx->sched_valid = false;  // lengths change: an attention schedule no longer holds
   const int span = ctx->cfg.max_pages_per_seq > ctx->cfg.max_nodes ? ctx->cfg.max_pages_per_seq : ctx->cfg.max_nodes;
   hipLaunchKernelGGL(tim_plan_commit_kernel, dim3((span + 255) / 256, plan->n_seqs), dim3(256), 0, tim_hs(stream),
                      ctx->cfg, ctx->st, *plan);

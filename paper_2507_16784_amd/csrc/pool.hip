@@ -254,6 +254,7 @@ __global__ void __launch_bounds__(1024) tim_stats_kernel(tim_config cfg, tim_sta
 // ---- host entry points -----------------------------------------------------------------------
 extern "C" int tim_pool_reset(tim_ctx *ctx, tim_stream stream) {
   if (!ctx || !ctx->bound) return TIM_ERR_INVALID_ARG;
+  ctx->sched_valid = false;  // lengths change: an attention schedule no longer holds
   hipLaunchKernelGGL(tim_reset_kernel, dim3(256), dim3(256), 0, tim_hs(stream), ctx->cfg, ctx->st);
   TIM_LAUNCH_CHECK();
   return TIM_OK;
@@ -271,6 +272,7 @@ extern "C" int tim_tree_mark(tim_ctx *ctx, const int32_t *ops, int32_t n_ops, ti
 
 extern "C" int tim_seq_advance(tim_ctx *ctx, tim_stream stream) {
   if (!ctx || !ctx->bound) return TIM_ERR_INVALID_ARG;
+  ctx->sched_valid = false;  // lengths change: an attention schedule no longer holds
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
   hipLaunchKernelGGL(tim_advance_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st);
@@ -280,6 +282,7 @@ extern "C" int tim_seq_advance(tim_ctx *ctx, tim_stream stream) {
 
 extern "C" int tim_seq_extend(tim_ctx *ctx, const int32_t *counts, tim_stream stream) {
   if (!ctx || !ctx->bound || !counts) return TIM_ERR_INVALID_ARG;
+  ctx->sched_valid = false;  // lengths change: an attention schedule no longer holds
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
   hipLaunchKernelGGL(tim_extend_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st, counts);

@@ -23,6 +23,8 @@ struct tim_ctx {
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
+  bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
+  int sched_cpb = 0, sched_slots = 0;
   bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
   int timing_n = 0;
   std::vector<hipEvent_t> ev_start, ev_stop;

@@ -22,7 +22,7 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_seq_extend", "tim_kv_write", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
+           "tim_attn_schedule", "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
 
 
 class tim_config(C.Structure):
@@ -65,6 +65,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_prune_plan": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
         "tim_kv_compact": (C.c_int, [p, C.POINTER(tim_plan), i32, i32, p]),
         "tim_plan_commit": (C.c_int, [p, C.POINTER(tim_plan), p]),
+        "tim_attn_schedule": (C.c_int, [p, i32, p]),
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_decode_attn_append": (C.c_int, [p, i32, p, p, p, p, f32, i32, i32, p]),
         "tim_decode_attn_masked": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
@@ -227,6 +228,9 @@ class Context:
 
     def tim_plan_commit(self, plan: Plan):
         _check(lib().tim_plan_commit(self.handle, C.byref(plan.c), _stream()), "tim_plan_commit")
+
+    def tim_attn_schedule(self, max_seq_len: int = 0):
+        _check(lib().tim_attn_schedule(self.handle, max_seq_len, _stream()), "tim_attn_schedule")
 
     def tim_decode_attn(self, layer: int, q: torch.Tensor, out: torch.Tensor, sm_scale: float, max_seq_len: int = 0):
         assert q.dtype == torch.bfloat16 and q.is_cuda and q.is_contiguous()

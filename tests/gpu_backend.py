@@ -35,6 +35,8 @@ class GpuRuntime:
         self.dev = self.ctx.seq_len.device
         self.max_len_hint = 0
         self.fused_append = False      # True: append + attention of a layer go out as one call
+        self.scheduled = False         # True: tim_attn_schedule before the first attention call after lengths changed
+        self._sched_fresh = False
         self._pending = {}
 
     # ---- inputs ------------------------------------------------------------------
@@ -44,8 +46,14 @@ class GpuRuntime:
     def _bf16(self, bits):
         return tensors.from_bits(bits).to(self.dev)
 
+    def _schedule(self):
+        if self.scheduled and not self._sched_fresh:
+            self.ctx.tim_attn_schedule(self.max_len_hint)
+            self._sched_fresh = True
+
     def load_state(self, tables, free_ids, seq_lens):
         c = self.ctx
+        self._sched_fresh = False
         c.page_table.fill_(-1)
         for b, t in enumerate(tables):
             c.page_table[b, : len(t)] = self._i32(t)
@@ -71,9 +79,11 @@ class GpuRuntime:
     def advance(self):
         self._settle()
         self.ctx.tim_seq_advance()
+        self._sched_fresh = False
 
     def extend_seq(self, counts):
         self.ctx.tim_seq_extend(self._i32(counts))
+        self._sched_fresh = False
 
     def write_rows(self, layer, counts, k_rows_bits, v_rows_bits):
         off = np.concatenate([[0], np.cumsum(np.asarray(counts, dtype=np.int64))]).astype(np.int32)
@@ -103,12 +113,14 @@ class GpuRuntime:
 
     def commit(self, plan):
         self.ctx.tim_plan_commit(plan)
+        self._sched_fresh = False
 
     def plan_view(self):
         return GpuPlanView(self.plan, self._n_flush)
 
     def decode_attn(self, layer, q_bits, sm_scale, out_dtype=torch.float32):
         out = torch.empty((self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim), dtype=out_dtype, device=self.dev)
+        self._schedule()
         if layer in self._pending:
             k, v = self._pending.pop(layer)
             self.ctx.tim_decode_attn_append(layer, self._bf16(q_bits), k, v, out, sm_scale, self.max_len_hint)
@@ -121,6 +133,7 @@ class GpuRuntime:
 
     def decode_attn_masked(self, layer, q_bits, sm_scale, out_dtype=torch.float32):
         out = torch.empty((self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim), dtype=out_dtype, device=self.dev)
+        self._schedule()
         self.ctx.tim_decode_attn_masked(layer, self._bf16(q_bits), out, sm_scale, self.max_len_hint)
         return out.float().cpu().numpy()
 

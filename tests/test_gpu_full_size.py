@@ -114,6 +114,7 @@ def test_config3_full_size_sampled():
         ctx.tim_seq_advance()
         same_state()
         hint = int(ora.seq_len.max())
+        ctx.tim_attn_schedule(hint)                                                    # as bench.py does, once per step
         for layer in sample_layers:
             q, kn, vn = rnd(64, 32, 128), rnd(64, 8, 128), rnd(64, 8, 128)
             ctx.tim_decode_attn_append(layer, q, kn, vn, out, shape.q_scale, hint)     # as bench.py launches it

@@ -144,11 +144,13 @@ def check_kv(ora, gpu, drift_ok=False, oracle_is_ahead=False):
     assert same >= 0.99 * tot
 
 
-def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1, fused=False):
+def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1, fused=False,
+           scheduled=False):
     ora = OracleRuntime(cfg, threshold)
     harness.preload_oracle(ora, wl, seed, kv_scale)
     gpu = gb.GpuRuntime(cfg, threshold)
     gpu.fused_append = fused
+    gpu.scheduled = scheduled
     gb.preload_gpu(gpu, wl, seed, kv_scale)
     check_state(ora, gpu)
     check_kv(ora, gpu)
@@ -205,7 +207,7 @@ def test_many_small_events_multi_layer_batch(gb, threshold, cadence):
     traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
     wl = Workload(traces, p0s, steps, every(cadence, steps, 3))
     cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=40)
-    replay(gb, wl, cfg, threshold, 5, 1.0, 128 ** -0.5)
+    replay(gb, wl, cfg, threshold, 5, 1.0, 128 ** -0.5, scheduled=threshold == 1)
 
 
 def test_config2_long_single_sequence(gb):
@@ -226,7 +228,7 @@ def test_config4_prune_heavy_recycling(gb):
     wl = Workload(traces, [p0] * 4, steps, every(2, steps, 4))
     used = 4 * ((p0 + 15) // 16)
     cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=used // 4)
-    ora, _ = replay(gb, wl, cfg, 2, 9, 1.0, 128 ** -0.5, attend_every=16, kv_check_every=8)
+    ora, _ = replay(gb, wl, cfg, 2, 9, 1.0, 128 ** -0.5, attend_every=16, kv_check_every=8, scheduled=True)
     assert ora.seq_len.max() < p0
 
 
@@ -256,7 +258,7 @@ def test_seeded_shape_sweep(gb, case):
     kv_scale = float(rng.choice([1.0, 128 ** -0.5]))
     sm_scale = float(rng.choice([128 ** -0.5, 0.02, 0.3]))
     replay(gb, wl, cfg, threshold, 3000 + case, kv_scale, sm_scale, attend_every=int(rng.randint(1, 4)),
-           fused=bool(rng.randint(2)))
+           fused=bool(rng.randint(2)), scheduled=case % 2 == 1)
 
 
 @pytest.mark.parametrize("n", [1, 15, 16, 17, 255, 256, 257, 1031])
@@ -292,6 +294,66 @@ def test_attention_lengths_and_needle(gb, n):
         got16 = gpu.decode_attn(0, q[0], 1.0, out_dtype=torch.bfloat16)
         assert np.all(np.abs(got16 - want) <= 2e-2 + 1e-2 * np.abs(want))
         assert gpu.status() == 0
+
+
+@pytest.mark.parametrize("page_size", [16, 1])
+def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
+    """tim_attn_schedule: one long sequence among short and empty ones (the case it exists for), every
+    variant of the attention call, against the oracle and against the unscheduled calls; then a length
+    changed behind the library's back must be reported, not followed out of bounds."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    lens = [300, 9000, 17, 0, 2500, 1, 4096, 16, 700, 0, 33]
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * len(lens), lens, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=16 * (16 // page_size),
+                              page_size=page_size)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 77, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    gb.preload_gpu(gpu, wl, 77, 1.0)
+    from oracle import attention, bf16
+
+    def definition(q_bits):                            # the library defines the output of an empty sequence as zero
+        out = np.zeros((len(lens), 8, 128), dtype=np.float32)
+        for b in range(len(lens)):
+            if ora.seq_len[b] > 0:
+                kb, vb = ora.gather_kv(0, b)
+                out[b] = attention.attend(bf16.to_f64(q_bits[b]), bf16.to_f64(kb), bf16.to_f64(vb), 128 ** -0.5)
+        return out
+
+    q, k, v = harness.step_inputs(77, 0, cfg, 1.0)
+    want = definition(q[0])
+    plain = gpu.decode_attn(0, q[0], 128 ** -0.5)
+    check_attention(plain, want)
+    gpu.scheduled = True
+    for hint in (0, max(lens), 100):                 # full tables, exact bound, a bound that is too small
+        gpu.max_len_hint = hint
+        gpu._sched_fresh = False
+        got = gpu.decode_attn(0, q[0], 128 ** -0.5)
+        check_attention(got, want)
+        assert np.allclose(got, plain, atol=1e-3 * np.abs(want).max())
+        got16 = gpu.decode_attn(0, q[0], 128 ** -0.5, out_dtype=torch.bfloat16)
+        assert np.all(np.abs(got16 - want) <= 2e-2 + 1e-2 * np.abs(want))
+        assert np.all(got[3] == 0) and np.all(got[9] == 0)               # empty sequences: zero output
+    assert gpu.status() == 0
+    # one decode step through the library's own calls: the schedule lapses at the advance and is rebuilt
+    gpu.fused_append = True
+    harness.run_step(ora, wl, 0, 77, 1.0, 128 ** -0.5, attend=False)
+    got = harness.run_step(gpu, wl, 0, 77, 1.0, 128 ** -0.5)
+    check_attention(got[0], definition(harness.step_inputs(77, 0, cfg, 1.0)[0][0]))
+    check_state(ora, gpu)
+    assert gpu.status() == 0
+    # stale schedule: lengths altered directly
+    gpu.decode_attn(0, q[0], 128 ** -0.5)
+    gpu.ctx.seq_len[1] = 5000
+    gpu.ctx.seq_len[2] = 7
+    gpu.decode_attn(0, q[0], 128 ** -0.5)
+    from paper_2507_16784_amd import tim
+    assert gpu.status() == tim.ERR_INVALID_ARG
+    gpu._sched_fresh = False                                             # scheduled again: fine again
+    ora.seq_len[1], ora.seq_len[2] = 5000, 7
+    check_attention(gpu.decode_attn(0, q[0], 128 ** -0.5), definition(q[0]))
+    assert gpu.status() == 0
 
 
 def test_pool_exhaustion_and_full_table_are_atomic(gb):
@@ -834,6 +896,7 @@ def test_decode_step_captured_in_a_hip_graph(gb):
 
     def step_calls():
         ctx.tim_seq_advance()
+        ctx.tim_attn_schedule(512)                     # part of the step: its work list is rebuilt on every replay
         for l in range(2):
             ctx.tim_decode_attn_append(l, q[l], kn[l], vn[l], outs[l], 128 ** -0.5, 512)
 
