@@ -178,7 +178,6 @@ __device__ __forceinline__ int at_slots_used(int n, int cpb, int slots) {
 // loads, at the end of the grid, while the last busy ones still run.
 struct AtWork {
   int b, kvh, slot, n, used;
-  int n_live;  // the sequence's length as it is now: differs from n only under a stale schedule
 };
 template <bool OUT_BF16>
 __device__ __forceinline__ bool at_take_work(const tim_config &cfg, const tim_state &st, const AttnWs &ws, void *out,
@@ -186,22 +185,23 @@ __device__ __forceinline__ bool at_take_work(const tim_config &cfg, const tim_st
   // Everything here is wave-uniform and must stay on the scalar path: a vector load issued by a new
   // workgroup queues behind the tile loads its CU already has in flight (measured: 2.5 us more per idle
   // workgroup).  Hence no store or atomic before the last of these loads - the compiler would then no
-  // longer trust the scalar cache - and the stale-schedule report is left to the caller (at_check_live).
+  // longer trust the scalar cache - and the stale-schedule check waits until the block's end (at_check_live).
   wk.kvh = blockIdx.x % cfg.kv_heads;
   if (ws.sched != nullptr) {
     const int item = blockIdx.x / cfg.kv_heads;  // below batch * slots, the list's capacity
     const int total = ws.sched[0];
-    const int4 e = reinterpret_cast<const int4 *>(ws.sched + AT_SCHED_HDR)[item];
+    int4 e = reinterpret_cast<const int4 *>(ws.sched + AT_SCHED_HDR)[item];
+    // both loads are on their way before either is used: one round trip, as without a schedule
+    asm("" : "+s"(e.x), "+s"(e.y), "+s"(e.z), "+s"(e.w) : "s"(total));
     if (item >= total) return false;
     wk.b = e.x;
     wk.slot = e.y;
     wk.n = e.z;
     wk.used = e.w;
-    wk.n_live = st.seq_len[wk.b];
   } else {
     wk.b = blockIdx.x / cfg.kv_heads;
     wk.slot = blockIdx.y;
-    wk.n = wk.n_live = st.seq_len[wk.b];
+    wk.n = st.seq_len[wk.b];
     wk.used = at_slots_used(wk.n, cpb, slots);
     if (wk.slot >= max(wk.used, 1)) return false;
   }
@@ -211,10 +211,10 @@ __device__ __forceinline__ bool at_take_work(const tim_config &cfg, const tim_st
   }
   return true;
 }
-// A length that changed since the schedule was written is reported; the stale one stays in use (every page
-// id is checked before it is dereferenced, so the worst outcome is a wrong output).
-__device__ __forceinline__ void at_check_live(const tim_state &st, const AtWork &wk) {
-  if (wk.n_live != wk.n) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+// A length that changed since the schedule was written is reported; the stale one was used (every page id is
+// checked before it is dereferenced, so the worst outcome is a wrong output).
+__device__ __forceinline__ void at_check_live(const tim_state &st, const AttnWs &ws, int b, int n) {
+  if (ws.sched != nullptr && st.seq_len[b] != n) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
 }
 
 template <bool OUT_BF16>
@@ -228,7 +228,6 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
 
   AtWork wk;
   if (!at_take_work<OUT_BF16>(cfg, st, ws, out, slots, cpb, wk)) return;
-  at_check_live(st, wk);
   const int b = wk.b, kvh = wk.kvh, slot = wk.slot, n = wk.n, used = wk.used;
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
@@ -331,6 +330,7 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
     for (int e2 = 0; e2 < 8; ++e2) red_o[sidx][h][8 * c + e2] = acc[h][e2];
   }
   __syncthreads();
+  at_check_live(st, ws, b, n);
   at_finish<AT_WAVES * 4, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
                                     used);
 }
@@ -380,7 +380,6 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   };
   int next_pid = 0;
   if (!PS1) next_pid = load_pids(slot);
-  at_check_live(st, wk);
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
 
@@ -595,6 +594,7 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       for (int mf = 0; mf < 8; ++mf) red_o[w][r][8 * lane + mf] = acc[mf][r];
   }
   __syncthreads();
+  at_check_live(st, ws, b, n);
   at_finish<AT_WAVES, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
                                 used);
 }
