@@ -126,8 +126,8 @@ def run_steps(torch, tim, ctx, plan, shape, wl, staged, n_steps, layers_run, rec
             _, s0, host = pending.pop(0)
             hint_len, hint_step = int(host.max()), s0
         hint = hint_len + (step - hint_step) + 1
-        if SCHEDULE:                                 # once per step: the layers' launches take only the slots in use
-            ctx.tim_attn_schedule(hint)
+        if SCHEDULE and B > 1:                       # once per step: the layers' launches take only the slots in use
+            ctx.tim_attn_schedule(hint)              # (the library ignores it for one sequence: spare the host call)
         for layer in range(layers_run):
             la = layer % L_alloc
             if flush_kind == "mask":

@@ -22,6 +22,7 @@
 #define AT_CHUNK_PAGES 16
 #define AT_PAGES_PER_WAVE (AT_CHUNK_PAGES / AT_WAVES)
 #define AT_MAX_SLOTS 128
+#define AT_BLOCKS_PER_CU 3  // of the matrix-core kernel: what its registers allow
 #define AT_NEG_BIG (-1.0e30f)
 
 __device__ __forceinline__ float at_bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -359,7 +360,7 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
 #define AT_LAZY_MAX 8.0f
 
 template <bool OUT_BF16, bool MASKED, bool PS1>
-__global__ void __launch_bounds__(AT_THREADS, 3)
+__global__ void __launch_bounds__(AT_THREADS, AT_BLOCKS_PER_CU)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
                              void *__restrict__ out, float scale_log2, int cpb, int slots,
                              const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new) {
@@ -722,6 +723,14 @@ tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sch
 extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream) {
   if (!ctx || !ctx->bound || max_seq_len < 0) return TIM_ERR_INVALID_ARG;
   at_shape(ctx, max_seq_len, &ctx->sched_cpb, &ctx->sched_slots);
+  // Nothing to gain when every block of the bound's grid is resident at once (idle blocks then cost nothing,
+  // and on configuration 4, 117 MB per launch, the list's order paired blocks on CUs worse than the grid's:
+  // 29.5 vs 27.0 us per launch), or when there is one sequence: the calls then run unscheduled.
+  ctx->sched_valid = false;
+  if (!ctx->sched_force &&
+      (ctx->cfg.max_batch == 1 ||
+       (int64_t)ctx->cfg.max_batch * ctx->cfg.kv_heads * ctx->sched_slots <= (int64_t)AT_BLOCKS_PER_CU * ctx->n_cu))
+    return TIM_OK;
   int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
   hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3((ctx->cfg.max_batch + 255) / 256), dim3(256), 0, tim_hs(stream),
                      ctx->cfg, ctx->st, sched, ctx->sched_slots, ctx->sched_cpb);

@@ -32,6 +32,8 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
     const int x = std::atoi(v);
     if (x >= 1 && x <= 64) c->attn_cpb = x;
   }
+  if (const char *v = std::getenv("TIM_ATTN_SCHED_FORCE"))  // tests: small shapes must reach the scheduled path too
+    c->sched_force = std::atoi(v) != 0;
   if (const char *v = std::getenv("TIM_ATTN_IMPL"))  // debugging / A-B measurement only
     c->attn_impl = std::strcmp(v, "valu") == 0 ? 0 : 1;
   int dev = 0;

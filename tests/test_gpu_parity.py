@@ -356,6 +356,28 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
     assert gpu.status() == 0
 
 
+def test_schedule_is_left_out_where_it_cannot_pay(gb, monkeypatch):
+    """Without the tests' override, a launch whose whole grid fits the chip at once stays unscheduled:
+    tim_attn_schedule returns success and does nothing, and a later change of a length is no error."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    monkeypatch.setenv("TIM_ATTN_SCHED_FORCE", "0")
+    lens = [700, 40, 2000]
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * 3, lens, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=8)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 78, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    gb.preload_gpu(gpu, wl, 78, 1.0)
+    gpu.scheduled = True
+    q, _, _ = harness.step_inputs(78, 0, cfg, 1.0)
+    check_attention(gpu.decode_attn(0, q[0], 128 ** -0.5), ora.decode_attn(0, q[0], 128 ** -0.5))
+    gpu.ctx.seq_len[2] = 1500                            # no schedule in force: nothing is stale
+    ora.seq_len[2] = 1500
+    check_attention(gpu.decode_attn(0, q[0], 128 ** -0.5), ora.decode_attn(0, q[0], 128 ** -0.5))
+    assert gpu.status() == 0
+
+
 def test_pool_exhaustion_and_full_table_are_atomic(gb):
     from paper_2507_16784_amd import tim
     from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
