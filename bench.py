@@ -353,6 +353,54 @@ def horizon_mode(torch, tim, np, configs, args):
     print(json.dumps(res), flush=True)
 
 
+def mix_mode(torch, tim, np):
+    """One decode-attention launch (configuration-3 geometry, one layer) on a batch of very unequal
+    lengths: k sequences that have not been flushed yet among 64 - k that have.  Kernel time from the
+    dispatch's own events, without and with the per-step work list."""
+    B, HQ, HKV, LONG, SHORT = 64, 32, 8, 32000, 2500
+    num_pages = 70000
+    ctx = tim.Context(1, HQ, HKV, num_pages, B, 2064, 1)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    q = torch.randn(B, HQ, 128, generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.zeros(B, HQ, 128, device="cuda", dtype=torch.bfloat16)
+    perm = torch.randperm(num_pages, generator=g, device="cuda").to(torch.int32)
+    rows = []
+    for k in (0, 1, 2, 4, 8, 16, 32, 64):
+        lens = [LONG] * k + [SHORT] * (B - k)
+        if sum((n + 15) // 16 for n in lens) > num_pages:
+            continue
+        at = 0
+        ctx.page_table.fill_(-1)
+        for b, n in enumerate(lens):
+            pages = (n + 15) // 16
+            ctx.page_table[b, :pages] = perm[at:at + pages]
+            at += pages
+        ctx.seq_len.copy_(torch.tensor(lens, dtype=torch.int32))
+        gb = sum(lens) * HKV * 128 * 2 * 2 / 1e9
+        row = {"long_sequences": k, "GB_per_launch": round(gb, 3)}
+        for name in ("unscheduled", "scheduled"):
+            ctx.tim_seq_extend(torch.zeros(B, dtype=torch.int32, device="cuda"))      # adds nothing; any schedule lapses
+            if name == "scheduled":
+                ctx.tim_attn_schedule(max(lens))
+            for _ in range(3):
+                ctx.tim_decode_attn(0, q, out, 0.088, max(lens))
+            torch.cuda.synchronize()
+            ctx.tim_timing_begin(32)
+            for _ in range(30):
+                ctx.tim_decode_attn(0, q, out, 0.088, max(lens))
+            us = float(np.mean(ctx.tim_timing_end())) * 1e3
+            row[name + "_us"] = round(us, 1)
+            row[name + "_GBps"] = round(gb / us * 1e6, 0)
+        assert ctx.tim_status() == 0
+        rows.append(row)
+        log(f"[bench] {row}")
+    print(json.dumps({"metric": "decode attention launch on mixed lengths, main kernel", "unit": "us per launch", "n_gpus": 1,
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "mixed-lengths", "batch": B, "layers": 1, "q_heads": HQ, "kv_heads": HKV,
+                                 "long_tokens": LONG, "short_tokens": SHORT}, "rows": rows}))
+
+
 def sweep_mode(torch, tim, np, ctx, plan, shape, wl, staged, initial, args):
     """Synthetic analogue of the paper's throughput-vs-pruning-buffer figure: the same window
     with thresholds 0/1/2/4 under flush-by-compaction and under in-forward masking, and
@@ -403,11 +451,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-schedule", action="store_true", help="A/B: leave out the per-step tim_attn_schedule call")
     ap.add_argument("--dump", default="", help="write per-step lengths and attention timings to this .npz")
-    ap.add_argument("--mode", default="window", choices=["window", "flush", "sweep"],
+    ap.add_argument("--mode", default="window", choices=["window", "flush", "sweep", "mix"],
                     help="window: the decode window (default, the headline number); flush: all big flushes in one "
                          "call, timing plan / compaction / commit, then the extend attention of Eq. 1 on the same plan; "
                          "sweep: the window for pruning-buffer thresholds 0/1/2/4, without pruning, and with the "
-                         "in-forward (masking) variant")
+                         "in-forward (masking) variant; mix: one attention launch on k sequences of 32,000 tokens "
+                         "among 64 - k of 2,500, with and without tim_attn_schedule")
     ap.add_argument("--workload", default="config3", choices=["config3", "config2", "config4", "config5"],
                     help="config3 is the headline workload; the others are reported for the record")
     ap.add_argument("--graph", action="store_true",
@@ -441,6 +490,9 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     t_setup = time.perf_counter()
+    if args.mode == "mix":
+        mix_mode(torch, tim, np)
+        return
     if args.workload == "config5":
         horizon_mode(torch, tim, np, configs, args)
         return
