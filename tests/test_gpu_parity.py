@@ -714,7 +714,7 @@ def test_wide_batch_exceeds_one_scan_pass(gb):
     traces = [base[i % 16] for i in range(nseq)]
     wl = Workload(traces, p0s, steps, {3: list(range(nseq)), 9: list(range(0, nseq, 3))})
     cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=3000)
-    replay(gb, wl, cfg, 0, 11, 1.0, 128 ** -0.5, attend_every=6, kv_check_every=1, fused=True)
+    replay(gb, wl, cfg, 0, 11, 1.0, 128 ** -0.5, attend_every=6, kv_check_every=1, fused=True, scheduled=True)
 
 
 def test_one_sequence_longer_than_the_slot_cap(gb):
@@ -730,6 +730,7 @@ def test_one_sequence_longer_than_the_slot_cap(gb):
     gb.preload_gpu(gpu, wl, 2, 1.0)
     for step in range(2):
         gpu.fused_append = step == 1
+        gpu.scheduled = step == 1                      # the work list then holds the capped number of slots
         want = harness.run_step(ora, wl, step, 2, 1.0, 128 ** -0.5)
         got = harness.run_step(gpu, wl, step, 2, 1.0, 128 ** -0.5)
         check_attention(got[0], want[0])
