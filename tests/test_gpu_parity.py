@@ -588,6 +588,7 @@ def test_in_forward_masked_variant(gb, threshold, cadence, spec_name, page_size)
     harness.preload_oracle(ora, wl, 4, 1.0)
     gpu = gb.GpuRuntime(cfg, threshold)
     gb.preload_gpu(gpu, wl, 4, 1.0)
+    gpu.scheduled = threshold == 2                   # the masked kernel also runs from a work list
     hidden = 0
     for step in range(steps):
         ops = wl.step_ops(step)
