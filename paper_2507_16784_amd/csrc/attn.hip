@@ -194,7 +194,7 @@ __device__ __forceinline__ bool at_take_work(const tim_config &cfg, const tim_st
     int4 e = reinterpret_cast<const int4 *>(ws.sched + AT_SCHED_HDR)[item];
     // both loads are on their way before either is used: one round trip, as without a schedule
     asm("" : "+s"(e.x), "+s"(e.y), "+s"(e.z), "+s"(e.w) : "s"(total));
-    if (item >= total) return false;
+    if (item >= total || (unsigned)e.x >= (unsigned)cfg.max_batch) return false;  // (the list lies in caller-owned memory)
     wk.b = e.x;
     wk.slot = e.y;
     wk.n = e.z;
