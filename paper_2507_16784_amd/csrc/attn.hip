@@ -1,10 +1,12 @@
 // Split-K paged GQA decode attention (HBM-bound: 4096 B per live token per layer).
 //
-// Work decomposition.  grid = (batch * kv_heads, slots).  A sequence's pages are cut into
-// chunks of AT_CHUNK_PAGES pages; block `slot` takes chunks slot, slot + slots, ... and
-// accumulates them into one partial (m, l, o[128]) per query head of its group.  Inside a
-// chunk each of the four waves streams its own run of pages.  Fixed-size chunks keep a
-// batch of very unequal lengths balanced: a long sequence simply occupies more blocks.
+// Work decomposition.  One block per (sequence, kv head, slot).  A sequence's pages are cut
+// into chunks of AT_CHUNK_PAGES pages; a sequence uses one slot per `cpb` chunks, and block
+// `slot` takes chunks slot, slot + used, ... and accumulates them into one partial
+// (m, l, o[128]) per query head of its group.  Inside a chunk each of the four waves
+// streams its own run of pages.  Fixed-size chunks keep a batch of very unequal lengths
+// balanced: a long sequence simply occupies more blocks.  Which blocks are launched, and in
+// which order, is at_take_work's business (a static grid, or the list tim_attn_schedule wrote).
 //
 // Wave mapping for one (page, kv head) tile of 16 rows x 256 B, K and V alike: load j
 // (j = 0..3) is one 16-byte load per lane covering 1 KiB of the tile contiguously, so
