@@ -25,6 +25,7 @@
 #define AT_PAGES_PER_WAVE (AT_CHUNK_PAGES / AT_WAVES)
 #define AT_MAX_SLOTS 128
 #define AT_BLOCKS_PER_CU 3  // of the matrix-core kernel: what its registers allow
+#define AT_GRADE_MIN_ROUNDS 3
 #define AT_NEG_BIG (-1.0e30f)
 
 __device__ __forceinline__ float at_bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -625,7 +626,8 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
   const int n = st.seq_len[b];
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  const int used = min(slots, (nchunks + cpb - 1) / cpb);
+  const int used = ws.sched != nullptr ? ws.sched[AT_SCHED_HDR + 4 * (int64_t)cfg.max_batch * AT_MAX_SLOTS + b]
+                                       : min(slots, (nchunks + cpb - 1) / cpb);
   if (used == 1) return;  // written by the partial kernel
   if (used == 0) {        // empty working memory: defined as zero
     at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, 0.f);
@@ -681,7 +683,7 @@ static int64_t at_partials_words(const tim_config &cfg) {
 extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
   if (!cfg) return 0;
   return at_partials_words(*cfg) * (int64_t)sizeof(float) +
-         (AT_SCHED_HDR + 4 * (int64_t)cfg->max_batch * AT_MAX_SLOTS) * (int64_t)sizeof(int32_t);
+         (AT_SCHED_HDR + (4 * (int64_t)AT_MAX_SLOTS + 1) * cfg->max_batch) * (int64_t)sizeof(int32_t);
 }
 
 // Launch shape for a bound on the longest sequence: chunks per block and slots.
@@ -702,24 +704,53 @@ static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int 
   *slots_out = slots;
 }
 
-// The work list of at_take_work: thread b places the items of sequence b behind those of every longer
-// sequence (ties: lower index first).  Quadratic in the batch, which is a few thousand at most.
-__global__ void __launch_bounds__(256)
-tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sched, int slots, int cpb) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= cfg.max_batch) return;
-  const int n = st.seq_len[b];
-  const int used = at_slots_used(n, cpb, slots);
-  int before = 0, total = 0;
-  for (int o = 0; o < cfg.max_batch; ++o) {
-    const int no = st.seq_len[o];
-    const int items = max(at_slots_used(no, cpb, slots), 1);
-    total += items;
-    if (no > n || (no == n && o < b)) before += items;
+// The work list of at_take_work.  One block; thread b (and b + blockDim.x, ...) handles sequence b; quadratic in
+// the batch, which is a few thousand at most.  Order: longest sequence first (ties: lower index first).
+// Block sizes are graded along the list when it holds at least AT_GRADE_MIN_ROUNDS rounds of work (a round =
+// what the chip's resident blocks take at cpb chunks each): a sequence that starts with more than grade_big / 16
+// rounds still to go gets blocks of 2 cpb chunks (fewer partial results, which cost far more than their size),
+// one that starts within the last grade_small / 16 rounds gets blocks of cpb / 2 (the launch ends on small
+// blocks), the rest cpb.
+// sched: [0] = number of items, items from word AT_SCHED_HDR on, then the slots each sequence uses
+// (the merge kernel's view of the same decision).
+__device__ __forceinline__ int at_chunks_of(int n) {
+  const int n_pages = (n + TIM_PS - 1) / TIM_PS;
+  return n > 0 ? (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES : 0;
+}
+__global__ void __launch_bounds__(1024)
+tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sched, int slots, int cpb, int grade_big,
+                         int grade_small, int round_chunks) {
+  int32_t *used_of = sched + AT_SCHED_HDR + 4 * (int64_t)cfg.max_batch * AT_MAX_SLOTS;
+  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
+    const int n = st.seq_len[b], c = at_chunks_of(n);
+    int64_t work_before = 0, work_total = 0;
+    for (int o = 0; o < cfg.max_batch; ++o) {
+      const int no = st.seq_len[o], co = at_chunks_of(no);
+      work_total += co;
+      if (no > n || (no == n && o < b)) work_before += co;
+    }
+    int per = cpb;
+    const int64_t to_go = work_total - work_before;
+    if (work_total >= (int64_t)AT_GRADE_MIN_ROUNDS * round_chunks) {
+      if (to_go * 16 > (int64_t)grade_big * round_chunks) per = 2 * cpb;
+      else if (to_go * 16 <= (int64_t)grade_small * round_chunks) per = max(cpb / 2, 1);
+    }
+    used_of[b] = min(slots, (c + per - 1) / per);
   }
-  if (b == 0) sched[0] = total;
-  int4 *items = reinterpret_cast<int4 *>(sched + AT_SCHED_HDR);
-  for (int s2 = 0; s2 < max(used, 1); ++s2) items[before + s2] = make_int4(b, s2, n, used);
+  __syncthreads();  // used_of is complete (global memory written and read by this block only)
+  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
+    const int n = st.seq_len[b], used = used_of[b];
+    int before = 0, total = 0;
+    for (int o = 0; o < cfg.max_batch; ++o) {
+      const int no = st.seq_len[o];
+      const int items = max(used_of[o], 1);
+      total += items;
+      if (no > n || (no == n && o < b)) before += items;
+    }
+    if (b == 0) sched[0] = total;
+    int4 *items = reinterpret_cast<int4 *>(sched + AT_SCHED_HDR);
+    for (int s2 = 0; s2 < max(used, 1); ++s2) items[before + s2] = make_int4(b, s2, n, used);
+  }
 }
 
 extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream) {
@@ -733,9 +764,17 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
       (ctx->cfg.max_batch == 1 ||
        (int64_t)ctx->cfg.max_batch * ctx->cfg.kv_heads * ctx->sched_slots <= (int64_t)AT_BLOCKS_PER_CU * ctx->n_cu))
     return TIM_OK;
+  if (ctx->grade_small > 0 && ctx->sched_cpb > 1) {  // the smallest blocks decide how many slots a sequence may need
+    const int per = ctx->sched_cpb / 2;
+    ctx->sched_slots = (ctx->sched_slots * ctx->sched_cpb + per - 1) / per;
+    if (ctx->sched_slots > AT_MAX_SLOTS) ctx->sched_slots = AT_MAX_SLOTS;
+  }
+  const int round_chunks = AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads * ctx->sched_cpb;
   int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
-  hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3((ctx->cfg.max_batch + 255) / 256), dim3(256), 0, tim_hs(stream),
-                     ctx->cfg, ctx->st, sched, ctx->sched_slots, ctx->sched_cpb);
+  int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
+  if (threads > 1024) threads = 1024;
+  hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st, sched,
+                     ctx->sched_slots, ctx->sched_cpb, ctx->grade_big, ctx->grade_small, round_chunks > 0 ? round_chunks : 1);
   TIM_LAUNCH_CHECK();
   ctx->sched_valid = true;
   return TIM_OK;

@@ -1,5 +1,6 @@
 // Context object: configuration, the caller's buffer pointers, host-side constants.
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -31,6 +32,13 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   if (const char *v = std::getenv("TIM_ATTN_CPB")) {  // tuning experiments only
     const int x = std::atoi(v);
     if (x >= 1 && x <= 64) c->attn_cpb = x;
+  }
+  if (const char *v = std::getenv("TIM_ATTN_GRADE")) {  // tuning experiments only: "big,small" in 1/16 rounds
+    int a = 0, b2 = 0;
+    if (std::sscanf(v, "%d,%d", &a, &b2) == 2 && a >= b2 && b2 >= 0) {
+      c->grade_big = a;
+      c->grade_small = b2;
+    }
   }
   if (const char *v = std::getenv("TIM_ATTN_SCHED_FORCE"))  // tests: small shapes must reach the scheduled path too
     c->sched_force = std::atoi(v) != 0;

@@ -42,6 +42,6 @@ def test_host_side_argument_checks_need_no_gpu():
     empty = tim.tim_state()
     assert lib.tim_bind(h, ctypes.byref(empty)) == tim.ERR_INVALID_ARG
     assert lib.tim_attn_schedule(h, 0, None) == tim.ERR_INVALID_ARG
-    # partials [batch][q_heads][128 slots][128 + 2] fp32, then the schedule: 4 words + 4 per (sequence, slot)
-    assert lib.tim_attn_ws_bytes(ctypes.byref(ok)) == 1 * 8 * 128 * 130 * 4 + (4 + 4 * 1 * 128) * 4
+    # partials [batch][q_heads][128 slots][128 + 2] fp32, then the schedule: 4 words, 4 per (sequence, slot), 1 per sequence
+    assert lib.tim_attn_ws_bytes(ctypes.byref(ok)) == 1 * 8 * 128 * 130 * 4 + (4 + (4 * 128 + 1) * 1) * 4
     assert lib.tim_ctx_destroy(h) == tim.OK
