@@ -280,8 +280,9 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
 /*
  * Optional, once per decode step after the lengths are final (after tim_seq_advance and any
  * flush): lists, in tim_state.attn_ws, the blocks the step's attention launches need - only
- * the slots each sequence really uses, longest sequence first - so that all decode-attention
- * calls up to the next change of a length launch exactly that work in that order.  The
+ * the slots each sequence really uses, longest sequence first, in larger blocks while much
+ * work is still to come and smaller ones at the end - so that all decode-attention calls up
+ * to the next change of a length launch exactly that work in that order.  The
  * split-K decomposition of Sec. 3.1's paged attention is otherwise sized for the longest
  * sequence, and a batch of very unequal lengths (working memories before and after their
  * flush) spends a good part of a launch on blocks that find nothing to do.  max_seq_len as
