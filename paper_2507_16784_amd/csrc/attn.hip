@@ -769,7 +769,8 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
     ctx->sched_slots = (ctx->sched_slots * ctx->sched_cpb + per - 1) / per;
     if (ctx->sched_slots > AT_MAX_SLOTS) ctx->sched_slots = AT_MAX_SLOTS;
   }
-  const int round_chunks = AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads * ctx->sched_cpb;
+  // (tests: a round of four items, so that small shapes reach all three block sizes)
+  const int round_chunks = (ctx->sched_force ? 4 : AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads) * ctx->sched_cpb;
   int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;

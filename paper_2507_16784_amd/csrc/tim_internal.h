@@ -26,7 +26,7 @@ struct tim_ctx {
   bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
   int sched_cpb = 0, sched_slots = 0;
   int grade_big = 32, grade_small = 8;  // graded block sizes along the schedule, in 1/16 rounds of work to go
-  bool sched_force = false;    // tests: schedule even where it cannot pay (TIM_ATTN_SCHED_FORCE=1)
+  bool sched_force = false;    // tests: schedule even where it cannot pay, grade even short lists (TIM_ATTN_SCHED_FORCE=1)
   bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
   int timing_n = 0;
   std::vector<hipEvent_t> ev_start, ev_stop;
