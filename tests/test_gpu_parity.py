@@ -336,6 +336,29 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
         assert np.all(np.abs(got16 - want) <= 2e-2 + 1e-2 * np.abs(want))
         assert np.all(got[3] == 0) and np.all(got[9] == 0)               # empty sequences: zero output
     assert gpu.status() == 0
+    # the work list itself (behind the partials in the workspace): every slot of every sequence once, longest
+    # sequence first, and - the tests' rounds being tiny - more than one block size in use
+    gpu.max_len_hint = max(lens)
+    gpu._sched_fresh = False
+    gpu.decode_attn(0, q[0], 128 ** -0.5)
+    ws = gpu.ctx.attn_ws.view(torch.int32).cpu().numpy()
+    base = len(lens) * 8 * 128 * 130
+    total = int(ws[base])
+    items = ws[base + 4: base + 4 + 4 * total].reshape(total, 4)        # sequence, slot, length, slots used
+    used_of = ws[base + 4 + 4 * len(lens) * 128: base + 4 + 4 * len(lens) * 128 + len(lens)]
+    order = [int(b) for b in dict.fromkeys(items[:, 0])]
+    assert sorted(order) == list(range(len(lens)))
+    assert [lens[b] for b in order] == sorted(lens, reverse=True)
+    chunk_sizes = set()
+    for b in range(len(lens)):
+        mine = items[items[:, 0] == b]
+        assert np.all(mine[:, 2] == lens[b]) and np.all(mine[:, 3] == used_of[b])
+        assert list(mine[:, 1]) == list(range(max(int(used_of[b]), 1)))
+        chunks = (lens[b] + 255) // 256
+        assert (used_of[b] == 0) == (lens[b] == 0) and used_of[b] <= max(chunks, 0)
+        if chunks >= 2:
+            chunk_sizes.add(-(-chunks // int(used_of[b])))
+    assert len(chunk_sizes) > 1, chunk_sizes
     # one decode step through the library's own calls: the schedule lapses at the advance and is rebuilt
     gpu.fused_append = True
     harness.run_step(ora, wl, 0, 77, 1.0, 128 ** -0.5, attend=False)
