@@ -52,7 +52,7 @@ __device__ __forceinline__ void at_unpack(const uint4 &u, float (&f)[8]) {
 }
 
 struct AttnWs {
-  float *ml;             // [B][Hq][slots][2]
+  float *ml;             // [B][Hkv][slots][4 heads][m, l]: the 32 bytes one block writes are contiguous
   float *o;              // [B][Hq][slots][128]
   const int32_t *sched;  // work list written by tim_attn_schedule, or nullptr (see at_take_work)
 };
@@ -92,6 +92,11 @@ __device__ __forceinline__ void at_store_through(uint32_t *p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ void at_store_through(float4 *p, const float4 &v) {
+  const at_f32x4 x = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(x) : "memory");
+}
+
 // Block epilogue shared by both variants.  The NS (m, l, o) states the block holds in LDS
 // are merged (log-sum-exp algebra).  If the block is the sequence's only one, the result is
 // final; otherwise it becomes this slot's partial for the merge kernel.  (Merging in the
@@ -118,6 +123,24 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     }
     return ot;
   };
+  // m and l of the block's four heads: one thread, two 16-byte stores into one 32-byte record (four 8-byte
+  // stores from four waves, each a partial line reaching memory on its own, cost 0.3 % of the whole kernel)
+  auto store_ml = [&]() {
+    float v[2 * TIM_G];
+#pragma unroll
+    for (int h = 0; h < TIM_G; ++h) {
+      float mx = AT_NEG_BIG, lt = 0.f;
+#pragma unroll
+      for (int s2 = 0; s2 < NS; ++s2) mx = fmaxf(mx, red_m[s2 * TIM_G + h]);
+#pragma unroll
+      for (int s2 = 0; s2 < NS; ++s2) lt = fmaf(red_l[s2 * TIM_G + h], __builtin_amdgcn_exp2f(red_m[s2 * TIM_G + h] - mx), lt);
+      v[2 * h] = mx;
+      v[2 * h + 1] = lt;
+    }
+    float4 *dst = reinterpret_cast<float4 *>(ws.ml + (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * (2 * TIM_G));
+    at_store_through(dst, make_float4(v[0], v[1], v[2], v[3]));
+    at_store_through(dst + 1, make_float4(v[4], v[5], v[6], v[7]));
+  };
   if (OUT_BF16 && used > 1) {
     // bf16 partial: thread -> head tid / 64, dims 2 (tid % 64) and the next one, one 32-bit word
     static_assert(AT_THREADS == TIM_G * TIM_D / 2, "one pair of dims per thread");
@@ -127,10 +150,7 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     const float inv = lt > 0.f ? 1.f / lt : 0.f;  // (a slot whose tokens are all hidden has l = 0)
     const int64_t pi = ((int64_t)b * cfg.q_heads + kvh * TIM_G + h) * slots + slot;
     at_store_through(reinterpret_cast<uint32_t *>(ws.o) + (pi * TIM_D + d0) / 2, at_pack_bf16(o0 * inv, o1 * inv));
-    if (d0 == 0) {
-      at_store_through(ws.ml + pi * 2, mx);
-      at_store_through(ws.ml + pi * 2 + 1, lt);
-    }
+    if (tid == 0) store_ml();
     return;
   }
 #pragma unroll
@@ -144,10 +164,7 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     } else {
       const int64_t pi = ((int64_t)b * cfg.q_heads + hq) * slots + slot;
       at_store_through(ws.o + pi * TIM_D + dim, ot);
-      if (dim == 0) {
-        at_store_through(ws.ml + pi * 2, mx);
-        at_store_through(ws.ml + pi * 2 + 1, lt);
-      }
+      if (idx == 0) store_ml();
     }
   }
 }
@@ -636,8 +653,10 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
   const int64_t p0 = (int64_t)bh * slots;
   float m = AT_NEG_BIG, l = 0.f;
   if (tid < used) {
-    m = ws.ml[(p0 + tid) * 2];
-    l = ws.ml[(p0 + tid) * 2 + 1];
+    const int hq = bh % cfg.q_heads;
+    const int64_t rec = (((int64_t)b * cfg.kv_heads + hq / TIM_G) * slots + tid) * (2 * TIM_G) + 2 * (hq % TIM_G);
+    m = ws.ml[rec];
+    l = ws.ml[rec + 1];
   }
   const float wm = at_wave_max(m);
   if ((tid & 63) == 0) red[tid >> 6] = wm;
