@@ -53,7 +53,7 @@ __device__ __forceinline__ void at_unpack(const uint4 &u, float (&f)[8]) {
 
 struct AttnWs {
   float *ml;             // [B][Hkv][slots][4 heads][m, l]: the 32 bytes one block writes are contiguous
-  float *o;              // [B][Hq][slots][128]
+  float *o;              // [B][Hkv][slots][4 heads][128] (fp32, or bf16 in half the bytes): 2 KiB or 1 KiB per block, contiguous
   const int32_t *sched;  // work list written by tim_attn_schedule, or nullptr (see at_take_work)
 };
 #define AT_SCHED_HDR 4  // words before the items: [0] = number of items; an item is {sequence, slot, length, slots used}
@@ -148,7 +148,7 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     float mx, lt, mx1, lt1;
     const float o0 = merged(h, d0, mx, lt), o1 = merged(h, d0 + 1, mx1, lt1);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;  // (a slot whose tokens are all hidden has l = 0)
-    const int64_t pi = ((int64_t)b * cfg.q_heads + kvh * TIM_G + h) * slots + slot;
+    const int64_t pi = (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * TIM_G + h;  // a block's four rows are contiguous
     at_store_through(reinterpret_cast<uint32_t *>(ws.o) + (pi * TIM_D + d0) / 2, at_pack_bf16(o0 * inv, o1 * inv));
     if (tid == 0) store_ml();
     return;
@@ -162,7 +162,7 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     if (used == 1) {
       at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, ot / lt);
     } else {
-      const int64_t pi = ((int64_t)b * cfg.q_heads + hq) * slots + slot;
+      const int64_t pi = (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * TIM_G + h;
       at_store_through(ws.o + pi * TIM_D + dim, ot);
       if (idx == 0) store_ml();
     }
@@ -650,7 +650,8 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
     at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, 0.f);
     return;
   }
-  const int64_t p0 = (int64_t)bh * slots;
+  // partial outputs: [B][Hkv][slots][4 heads][128]; slot s of this head is row p0 + s * TIM_G
+  const int64_t p0 = ((int64_t)b * cfg.kv_heads + (bh % cfg.q_heads) / TIM_G) * slots * TIM_G + (bh % cfg.q_heads) % TIM_G;
   float m = AT_NEG_BIG, l = 0.f;
   if (tid < used) {
     const int hq = bh % cfg.q_heads;
@@ -675,21 +676,21 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
     for (; s + 8 <= used; s += 8) {
       uint16_t v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
+      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * (TIM_G * TIM_D)];
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc = fmaf(__uint_as_float((uint32_t)v[u] << 16), wgt[s + u], acc);
     }
-    for (; s < used; ++s) acc = fmaf(__uint_as_float((uint32_t)o[(int64_t)s * TIM_D] << 16), wgt[s], acc);
+    for (; s < used; ++s) acc = fmaf(__uint_as_float((uint32_t)o[(int64_t)s * (TIM_G * TIM_D)] << 16), wgt[s], acc);
   } else {
     const float *o = ws.o + p0 * TIM_D + tid;
     for (; s + 8 <= used; s += 8) {
       float v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * TIM_D];
+      for (int u = 0; u < 8; ++u) v[u] = o[(int64_t)(s + u) * (TIM_G * TIM_D)];
 #pragma unroll
       for (int u = 0; u < 8; ++u) acc = fmaf(v[u], wgt[s + u], acc);
     }
-    for (; s < used; ++s) acc = fmaf(o[(int64_t)s * TIM_D], wgt[s], acc);
+    for (; s < used; ++s) acc = fmaf(o[(int64_t)s * (TIM_G * TIM_D)], wgt[s], acc);
   }
   at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, acc / lt);
 }
