@@ -422,15 +422,23 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   const uint4 *vpool = reinterpret_cast<const uint4 *>(st.v_pool);
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
+  // Page size 1: a "page" below is a run of 16 tokens and every row has its own page id.  The ids of a pair's
+  // 32 tokens are one load (lane l holds token 32 (pg / 2) + l % 32), requested one pair ahead like the page
+  // ids above, and handed to the lanes that need them by cross-lane reads.
+  auto load_row_ids = [&](int pg_) { return ptab[min(pg_ * TIM_PS + (lane & 31), n - 1)]; };
+  int next_ids = 0;
+  if (PS1) next_ids = load_row_ids(slot * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE);
+
   for (int chunk = slot; chunk < nchunks; chunk += used) {
     const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
     const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
     // the wave's page ids of this chunk: lane i holds page pg0 + i % 4; the next chunk's are requested now.
-    // (With page size 1 a "page" below is a run of 16 tokens and every row has its own page id.)
     const int my_pid = next_pid;
     if (!PS1) next_pid = load_pids(chunk + used);
     for (int pg = pg0; pg < pg1; pg += 2) {
       const bool has_b = pg + 1 < pg1;
+      int my_ids = next_ids;
+      if (PS1) next_ids = load_row_ids(pg + 2 < pg1 ? pg + 2 : (chunk + used) * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE);
       // in-forward variant: visibility of the pair's 32 tokens (pairs start at even pages);
       // a pair without a visible token is not read at all
       uint32_t vis = 0xffffffffu;
@@ -440,23 +448,21 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       }
       uint4 ka[4], kb[4], va[4], vb[4];
       if (PS1) {
-        // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  (Ordinary
-        // loads here: a 256-byte row is touched by four load instructions, and without the L1 they were slower.)
-        const int ta = pg * TIM_PS, tb = has_b ? ta + TIM_PS : ta, last = n - 1;
+        // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  K rows are read
+        // in 64-byte pieces by four instructions and need the L1 (ordinary loads; non-temporal ones measured 6 %
+        // slower); a V row is read whole by one instruction: non-temporal, +4 %.
+        if (my_ids < 0 || my_ids >= cfg.num_pages) {  // never dereference a bad page id
+          tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+          my_ids = 0;
+        }
+        const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
         int ids[10];
-        ids[0] = ptab[min(ta + j, last)];
-        ids[1] = ptab[min(tb + j, last)];
+        ids[0] = __shfl(my_ids, j, 64);
+        ids[1] = __shfl(my_ids, off_b + j, 64);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          ids[2 + i] = ptab[min(ta + 4 * g + i, last)];
-          ids[6 + i] = ptab[min(tb + 4 * g + i, last)];
-        }
-#pragma unroll
-        for (int i = 0; i < 10; ++i) {
-          if (ids[i] < 0 || ids[i] >= cfg.num_pages) {  // never dereference a bad page id
-            tim_set_status(st.status, TIM_ERR_INVALID_ARG);
-            ids[i] = 0;
-          }
+          ids[2 + i] = __shfl(my_ids, 4 * g + i, 64);
+          ids[6 + i] = __shfl(my_ids, off_b + 4 * g + i, 64);
         }
         const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
@@ -464,9 +470,9 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
 #pragma unroll
         for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = vpool[((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j];
+        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = vpool[((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j];
+        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
       } else {
         int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
         int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
