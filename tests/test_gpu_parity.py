@@ -401,6 +401,18 @@ def test_schedule_is_left_out_where_it_cannot_pay(gb, monkeypatch):
     assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("scheduled", [False, True])
+def test_vector_alu_attention_variant(gb, monkeypatch, scheduled):
+    """The attention kernel without matrix instructions (kept for A/B measurements, TIM_ATTN_IMPL=valu) takes
+    the same work assignment and epilogue: a few decode steps with a flush, unscheduled and scheduled."""
+    monkeypatch.setenv("TIM_ATTN_IMPL", "valu")
+    seeds, p0s, steps = [51, 52, 53], [2100, 40, 777], 10
+    traces = [generate(s, p + steps + 1, SPEC_C1) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(4, steps, 3, first=1))
+    cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=60)
+    replay(gb, wl, cfg, 1, 17, 1.0, 128 ** -0.5, fused=scheduled, scheduled=scheduled)
+
+
 def test_pool_exhaustion_and_full_table_are_atomic(gb):
     from paper_2507_16784_amd import tim
     from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
