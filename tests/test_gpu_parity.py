@@ -413,6 +413,30 @@ def test_vector_alu_attention_variant(gb, monkeypatch, scheduled):
     replay(gb, wl, cfg, 1, 17, 1.0, 128 ** -0.5, fused=scheduled, scheduled=scheduled)
 
 
+def test_kernel_timing_aid(gb):
+    """tim_timing_begin / _end: one positive duration per attention call up to the cap, none beyond it,
+    the same outputs as untimed calls, and a second window after the first."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    lens = [3000, 500]
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr, tr], lens, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=4)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 79, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0)
+    gb.preload_gpu(gpu, wl, 79, 1.0)
+    q, _, _ = harness.step_inputs(79, 0, cfg, 1.0)
+    want = ora.decode_attn(0, q[0], 128 ** -0.5)
+    for window in range(2):
+        gpu.ctx.tim_timing_begin(3)
+        outs = [gpu.decode_attn(0, q[0], 128 ** -0.5) for _ in range(5)]
+        ms = gpu.ctx.tim_timing_end()
+        assert len(ms) == 3 and all(0.0 < t < 100.0 for t in ms)
+        for o in outs:
+            check_attention(o, want)
+    assert gpu.status() == 0
+
+
 def test_pool_exhaustion_and_full_table_are_atomic(gb):
     from paper_2507_16784_amd import tim
     from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
