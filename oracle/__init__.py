@@ -15,6 +15,8 @@ HIP kernels or their Python binding, and never imports them.
 Parity pins (tests/test_oracle_*.py) cover every function here: the paper's
 worked example of Sec. 3.1, the Fig. 3 caption scenario, brute force on tiny
 trees, FIFO-vs-declarative agreement, the RoPE composition closed form,
-prune-nothing == causal attention, page conservation, and hand-worked
-allocator examples.  No function is "parity unpinned".
+prune-nothing == causal attention, page conservation, hand-worked allocator
+examples, and - for the runtime's extend and masked attention wrappers - rows
+of a library's dense causal attention per flushed sequence and a triple loop
+over the visible tokens.  No function is "parity unpinned".
 """
