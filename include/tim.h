@@ -26,7 +26,7 @@
  *     One context serves one stream at a time.
  *   - Shapes: head_dim = 128, q_heads = 4 * kv_heads, page_size = 16, or 1 (the paper's
  *     own setting, Sec. 3.1; see "Page size 1" below).  Other values are rejected with
- *     TIM_ERR_INVALID_ARG.
+ *     TIM_ERR_INVALID_ARG.  One pool layout (below) and one rotary pairing (half-split).
  *   - bf16 is the upper half of an IEEE binary32, round-to-nearest-even.
  *
  * Data layout
@@ -176,6 +176,32 @@ int tim_ctx_destroy(tim_ctx *ctx);
 int tim_bind(tim_ctx *ctx, const tim_state *state);
 
 /*
+ * Launch-shape parameters of the decode-attention calls (the split-K decomposition of
+ * Sec. 3.1's paged attention).  They change how the work is cut, never what is computed.
+ * tim_ctx_create installs the defaults measured on MI355X; a caller (a test that wants a
+ * small shape to reach every code path, an A/B measurement) reads them with
+ * tim_ctx_get_tuning, changes fields and installs them with tim_ctx_set_tuning, which
+ * rejects values outside the ranges given here with TIM_ERR_INVALID_ARG and lets any
+ * schedule lapse.  Host objects only; nothing is read from the environment.
+ */
+typedef enum { TIM_ATTN_VALU = 0, TIM_ATTN_MFMA = 1 } tim_attn_impl;
+typedef struct {
+  int32_t attn_impl;         /* TIM_ATTN_MFMA (default): both contractions on the matrix cores;
+                                TIM_ATTN_VALU: vector-ALU kernel with cross-lane reductions (16-token pages only) */
+  int32_t chunks_per_block;  /* 1..64, default 6: 256-token chunks one block accumulates */
+  int32_t fill;              /* 1..64, default 2: blocks shrink until the launch holds this many per CU */
+  int32_t grade_big;         /* default 32: under a schedule, a sequence that starts with more than grade_big/16
+                                rounds of work to go gets blocks of twice the size */
+  int32_t grade_small;       /* default 8, 0 <= grade_small <= grade_big: one that starts within the last
+                                grade_small/16 rounds gets blocks of half the size */
+  int32_t round_items;       /* default 0: a round is what the chip's resident blocks take.  > 0: a round is
+                                this many blocks, and tim_attn_schedule schedules even launches that fit the
+                                chip at once or hold one sequence (small shapes then reach all block sizes) */
+} tim_tuning;
+int tim_ctx_get_tuning(const tim_ctx *ctx, tim_tuning *out);
+int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *tuning);
+
+/*
  * Empties the context: free_stack[i] = num_pages-1-i (so the first pops hand out
  * pages 0, 1, 2, ...), free_top = num_pages, all sequences empty, page tables and
  * trees unset, status cleared.  The paper recycles pages of pruned tokens
@@ -196,8 +222,11 @@ int tim_pool_reset(tim_ctx *ctx, tim_stream stream);
 int tim_tree_mark(tim_ctx *ctx, const int32_t *ops, int32_t n_ops, tim_stream stream);
 
 /*
- * Reserves the slot of each sequence's pending token: a sequence whose length is
- * a multiple of 16 pops one page (sequences served in ascending id), then every
+ * Reserves the slot of each sequence's pending token (Sec. 3.1: while the cache is
+ * pruned the newest token x_k is still waiting to be encoded; its state h_k then
+ * joins the working memory as the last element, and the pages freed by pruning are
+ * the ones reused for it): a sequence whose length is
+ * a multiple of the page size pops one page (sequences served in ascending id), then every
  * length grows by one.  If the pool cannot serve the whole batch, or a page
  * table is full, nothing changes and status is set.
  */
@@ -224,7 +253,8 @@ int tim_kv_write(tim_ctx *ctx, int32_t layer, const int32_t *row_off, int32_t n_
 
 /*
  * Writes the pending token's key and value of one layer into slot seq_len-1 of
- * every sequence.  k_new, v_new: device bf16 [max_batch][kv_heads][128]; the key
+ * every sequence (Sec. 3.1, Eq. 1: h_k, the encoding of the pending token x_k, is
+ * appended behind the retained and repositioned states).  k_new, v_new: device bf16 [max_batch][kv_heads][128]; the key
  * is already rotated at position seq_len-1.
  */
 int tim_kv_append(tim_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, tim_stream stream);
@@ -255,9 +285,11 @@ int tim_prune_plan(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t
 int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_begin, int32_t layer_end, tim_stream stream);
 
 /*
- * Completes the flush: returns the replaced pages to the free stack (ascending
- * sequence, ascending logical page), installs the new page-table rows and
- * lengths, and moves every node boundary b of the flushed sequences to rank[b].
+ * Completes the flush (Sec. 1 and Sec. 3.1: the memory pages of pruned tokens are
+ * recycled for later decoding, and positions are reused): returns the replaced pages
+ * to the free stack (ascending sequence, ascending logical page), installs the new
+ * page-table rows and lengths, and moves every node boundary b of the flushed
+ * sequences to rank[b], so that the task tree stays in current coordinates.
  */
 int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream stream);
 
@@ -313,9 +345,10 @@ int tim_decode_attn_append(tim_ctx *ctx, int32_t layer, const void *q, const voi
  *   out[off_e + j - first_pruned][h] = softmax(sm_scale * q[..][h] . K[0..j]^T) V[0..j]
  * over the sequence's current cache, with off_e = TIM_HDR_EXT_OFF of row e.  q_ext: device
  * bf16 [TIM_TOT_EXT][q_heads][128], rotated at the new positions; out_ext: device, same
- * shape, out_dtype.  n_ext_total must equal the plan's TIM_TOT_EXT (the caller reads it
- * back to build the queries); a smaller value leaves the tail uncomputed, a larger one is
- * harmless.  Weight-free: it does not recompute K/V, it is the attention the re-encoding
+ * shape, out_dtype.  n_ext_total is the number of rows q_ext and out_ext hold; it must be at
+ * least the plan's TIM_TOT_EXT (the caller reads that back to build the queries).  Rows
+ * beyond TIM_TOT_EXT are left untouched; a smaller value writes nothing at all and sets
+ * TIM_ERR_INVALID_ARG in the status word.  Weight-free: it does not recompute K/V, it is the attention the re-encoding
  * would run, so its cost can be set against tim_kv_compact's re-rotation.
  */
 int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan, const void *q_ext, void *out_ext,
@@ -338,8 +371,16 @@ int tim_prune_mask(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t
 int tim_decode_attn_masked(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                            int32_t max_seq_len, tim_stream stream);
 
-/* out: device int32 [2] = (free pages, pages referenced by page tables). */
-int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream);
+/*
+ * Page accounting (Sec. 1: pages of pruned tokens are recycled, none may leak).
+ * out: device int32 [4] = (free pages; page-table entries that hold a page id, counted from
+ * the tables themselves; pages the lengths call for, sum of ceil(seq_len / page_size);
+ * 1 if some page id occurs twice among the free stack and the tables or lies outside the
+ * pool, else 0).  A healthy context has out[0] + out[1] == num_pages, out[1] == out[2],
+ * out[3] == 0.  The duplicate check runs only when scratch (device int32 [num_pages], any
+ * contents) is given; with scratch == NULL out[3] is -1.
+ */
+int tim_pool_stats(tim_ctx *ctx, int32_t *out, int32_t *scratch, tim_stream stream);
 
 /*
  * Benchmark aid: between tim_timing_begin and tim_timing_end the main kernel of every

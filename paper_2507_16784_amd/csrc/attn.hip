@@ -160,7 +160,8 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
     float mx, lt;
     const float ot = merged(h, dim, mx, lt);
     if (used == 1) {
-      at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, ot / lt);
+      // (in-forward variant: a working memory whose tokens are all hidden has l = 0; its output is defined as zero)
+      at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + hq) * TIM_D + dim, lt > 0.f ? ot / lt : 0.f);
     } else {
       const int64_t pi = (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * TIM_G + h;
       at_store_through(ws.o + pi * TIM_D + dim, ot);
@@ -698,7 +699,7 @@ tim_attn_merge_kernel(tim_config cfg, tim_state st, AttnWs ws, void *__restrict_
     }
     for (; s < used; ++s) acc = fmaf(o[(int64_t)s * (TIM_G * TIM_D)], wgt[s], acc);
   }
-  at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, acc / lt);
+  at_store_out<OUT_BF16>(out, (int64_t)bh * TIM_D + tid, lt > 0.f ? acc / lt : 0.f);  // all tokens hidden: zero
 }
 
 // words of the workspace that hold the partials; the schedule follows them
@@ -786,7 +787,7 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
   // and on configuration 4, 117 MB per launch, the list's order paired blocks on CUs worse than the grid's:
   // 29.5 vs 27.0 us per launch), or when there is one sequence: the calls then run unscheduled.
   ctx->sched_valid = false;
-  if (!ctx->sched_force &&
+  if (ctx->round_items == 0 &&
       (ctx->cfg.max_batch == 1 ||
        (int64_t)ctx->cfg.max_batch * ctx->cfg.kv_heads * ctx->sched_slots <= (int64_t)AT_BLOCKS_PER_CU * ctx->n_cu))
     return TIM_OK;
@@ -795,8 +796,9 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
     ctx->sched_slots = (ctx->sched_slots * ctx->sched_cpb + per - 1) / per;
     if (ctx->sched_slots > AT_MAX_SLOTS) ctx->sched_slots = AT_MAX_SLOTS;
   }
-  // (tests: a round of four items, so that small shapes reach all three block sizes)
-  const int round_chunks = (ctx->sched_force ? 4 : AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads) * ctx->sched_cpb;
+  // (a caller-set round of a few items lets small shapes reach all three block sizes)
+  const int round_chunks =
+      (ctx->round_items > 0 ? ctx->round_items : AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads) * ctx->sched_cpb;
   int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;

@@ -1,8 +1,5 @@
 // Context object: configuration, the caller's buffer pointers, host-side constants.
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
-#include <cstring>
 #include <new>
 
 #include "tim_internal.h"
@@ -22,34 +19,42 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   c->cfg = *cfg;
   c->bound = false;
   c->n_cu = 256;
-  c->attn_impl = 1;
+  c->attn_impl = TIM_ATTN_MFMA;
   c->attn_cpb = 6;  // 768 KiB of K/V per block; 5 to 8 measure within 0.5 % of each other on 16-32K-token sequences
   c->attn_fill = 2;
-  if (const char *v = std::getenv("TIM_ATTN_FILL")) {  // tuning experiments only
-    const int x = std::atoi(v);
-    if (x >= 1 && x <= 64) c->attn_fill = x;
-  }
-  if (const char *v = std::getenv("TIM_ATTN_CPB")) {  // tuning experiments only
-    const int x = std::atoi(v);
-    if (x >= 1 && x <= 64) c->attn_cpb = x;
-  }
-  if (const char *v = std::getenv("TIM_ATTN_GRADE")) {  // tuning experiments only: "big,small" in 1/16 rounds
-    int a = 0, b2 = 0;
-    if (std::sscanf(v, "%d,%d", &a, &b2) == 2 && a >= b2 && b2 >= 0) {
-      c->grade_big = a;
-      c->grade_small = b2;
-    }
-  }
-  if (const char *v = std::getenv("TIM_ATTN_SCHED_FORCE"))  // tests: small shapes must reach the scheduled path too
-    c->sched_force = std::atoi(v) != 0;
-  if (const char *v = std::getenv("TIM_ATTN_IMPL"))  // debugging / A-B measurement only
-    c->attn_impl = std::strcmp(v, "valu") == 0 ? 0 : 1;
   int dev = 0;
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
     c->n_cu = prop.multiProcessorCount;
   for (int i = 0; i < TIM_D / 2; ++i) c->inv_freq[i] = std::pow((double)cfg->rope_base, -2.0 * i / TIM_D);
   *out = c;
+  return TIM_OK;
+}
+
+extern "C" int tim_ctx_get_tuning(const tim_ctx *ctx, tim_tuning *out) {
+  if (!ctx || !out) return TIM_ERR_INVALID_ARG;
+  out->attn_impl = ctx->attn_impl;
+  out->chunks_per_block = ctx->attn_cpb;
+  out->fill = ctx->attn_fill;
+  out->grade_big = ctx->grade_big;
+  out->grade_small = ctx->grade_small;
+  out->round_items = ctx->round_items;
+  return TIM_OK;
+}
+
+extern "C" int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *t) {
+  if (!ctx || !t) return TIM_ERR_INVALID_ARG;
+  if ((t->attn_impl != TIM_ATTN_VALU && t->attn_impl != TIM_ATTN_MFMA) || t->chunks_per_block < 1 ||
+      t->chunks_per_block > 64 || t->fill < 1 || t->fill > 64 || t->grade_small < 0 || t->grade_big < t->grade_small ||
+      t->round_items < 0)
+    return TIM_ERR_INVALID_ARG;
+  ctx->attn_impl = t->attn_impl;
+  ctx->attn_cpb = t->chunks_per_block;
+  ctx->attn_fill = t->fill;
+  ctx->grade_big = t->grade_big;
+  ctx->grade_small = t->grade_small;
+  ctx->round_items = t->round_items;
+  ctx->sched_valid = false;  // a schedule written under the old shape no longer matches the launches
   return TIM_OK;
 }
 

@@ -86,10 +86,17 @@ __device__ __forceinline__ ex_bf16x8 ex_as_bf16x8(const uint4 &u) { return __bui
 typedef __attribute__((address_space(3))) unsigned char *exl_lds_ptr;
 typedef short exl_s16x4 __attribute__((ext_vector_type(4)));
 
-// 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base is wave-uniform)
+// 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base is wave-uniform).
+// The statement overwrites m0 and says so: the compiler sets m0 itself before each of its own uses
+// (LDS-DMA builtins, indexed register moves, messages) and merges such settings when it sees no
+// write between them, so an undeclared write here could leave a later use with this address.  m0 is
+// a reserved register, for which clang prints a generic caution; that is the one diagnostic silenced.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void exl_copy16(const void *src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ void exl_wait_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 // all but the four youngest copies of this wave (memory operations complete in order)
 __device__ __forceinline__ void exl_wait_older_copies() { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
@@ -110,7 +117,12 @@ tim_extend_attn_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, in
                            float scale_log2) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * EXL_RING * EXL_PAIR_BYTES];
   const int kvh = blockIdx.x;
-  if (!pl.totals[TIM_TOT_OK] || (int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
+  if (!pl.totals[TIM_TOT_OK]) return;
+  if (n_ext_total < pl.totals[TIM_TOT_EXT]) {  // the caller's buffers hold fewer rows than the plan extends: nothing is written
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+    return;
+  }
+  if ((int)blockIdx.y >= pl.totals[TIM_TOT_EXT_TILES]) return;
   const int tile = pl.totals[TIM_TOT_EXT_TILES] - 1 - blockIdx.y;
   int lo = 0, hi = n_seqs - 1;  // flushed sequence of this tile: last e with EXT_TILE_OFF[e] <= tile
   while (lo < hi) {
@@ -399,8 +411,7 @@ extern "C" int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan
       ctx->cfg.page_size != TIM_PS ||  // the extend kernel reads 16-token pages only
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16))
     return TIM_ERR_INVALID_ARG;
-  if (n_ext_total == 0) return TIM_OK;
-  if (!q_ext || !out_ext) return TIM_ERR_INVALID_ARG;
+  if (n_ext_total > 0 && (!q_ext || !out_ext)) return TIM_ERR_INVALID_ARG;  // (with no rows the kernel only checks the plan)
   // every sequence adds at most one partly filled tile
   const int tiles = (n_ext_total + EX_TILE_TOKENS - 1) / EX_TILE_TOKENS + plan->n_seqs;
   dim3 grid(ctx->cfg.kv_heads, tiles);

@@ -239,16 +239,36 @@ __global__ void tim_append_kernel(tim_config cfg, tim_state st, int layer, const
 }
 
 // ---- accounting ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(1024) tim_stats_kernel(tim_config cfg, tim_state st, int32_t *out) {
-  __shared__ int smem[17];
-  int cnt = 0;
-  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) cnt += (st.seq_len[b] + cfg.page_size - 1) / cfg.page_size;
-  int total;
-  tim_block_incl_scan(cnt, smem, &total);
-  if (threadIdx.x == 0) {
-    out[0] = *st.free_top;
-    out[1] = total;
+// Counted from the page tables themselves, not derived from the lengths, so that a leaked or doubly
+// pushed page, or a table entry that disagrees with its sequence's length, shows up on the device.
+__global__ void tim_stats_clear_kernel(tim_config cfg, int32_t *out, int32_t *seen) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+  if (seen)
+    for (int64_t k = i; k < cfg.num_pages; k += stride) seen[k] = 0;
+  if (i < 4) out[i] = (i == 3 && !seen) ? -1 : 0;
+}
+__global__ void __launch_bounds__(256) tim_stats_kernel(tim_config cfg, tim_state st, int32_t *out, int32_t *seen) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+  const int top = min(max(*st.free_top, 0), cfg.num_pages);
+  int entries = 0, by_len = 0, bad = 0;
+  auto visit = [&](int page) {
+    if (page < 0 || page >= cfg.num_pages) bad = 1;
+    else if (seen && atomicAdd(&seen[page], 1) != 0) bad = 1;
+  };
+  for (int64_t k = i; k < top; k += stride) visit(st.free_stack[k]);
+  const int64_t npt = (int64_t)cfg.max_batch * cfg.max_pages_per_seq;
+  for (int64_t k = i; k < npt; k += stride) {
+    const int page = st.page_table[k];
+    if (page != -1) {
+      ++entries;
+      visit(page);
+    }
   }
+  for (int64_t b = i; b < cfg.max_batch; b += stride) by_len += (st.seq_len[b] + cfg.page_size - 1) / cfg.page_size;
+  if (entries) atomicAdd(&out[1], entries);
+  if (by_len) atomicAdd(&out[2], by_len);
+  if (bad && seen) atomicOr(&out[3], 1);
+  if (i == 0) out[0] = *st.free_top;
 }
 
 // ---- host entry points -----------------------------------------------------------------------
@@ -315,9 +335,11 @@ extern "C" int tim_kv_append(tim_ctx *ctx, int32_t layer, const void *k_new, con
   return TIM_OK;
 }
 
-extern "C" int tim_pool_stats(tim_ctx *ctx, int32_t *out, tim_stream stream) {
+extern "C" int tim_pool_stats(tim_ctx *ctx, int32_t *out, int32_t *scratch, tim_stream stream) {
   if (!ctx || !ctx->bound || !out) return TIM_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(tim_stats_kernel, dim3(1), dim3(256), 0, tim_hs(stream), ctx->cfg, ctx->st, out);
+  hipLaunchKernelGGL(tim_stats_clear_kernel, dim3(64), dim3(256), 0, tim_hs(stream), ctx->cfg, out, scratch);
+  TIM_LAUNCH_CHECK();
+  hipLaunchKernelGGL(tim_stats_kernel, dim3(64), dim3(256), 0, tim_hs(stream), ctx->cfg, ctx->st, out, scratch);
   TIM_LAUNCH_CHECK();
   return TIM_OK;
 }

@@ -19,14 +19,15 @@ struct tim_ctx {
   tim_state st;
   bool bound;
   int n_cu;
-  int attn_impl;  // 1 = matrix-core attention (default), 0 = vector-ALU attention
+  int attn_impl;  // tim_attn_impl: matrix-core attention (default) or vector-ALU attention
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
   int sched_cpb = 0, sched_slots = 0;
   int grade_big = 32, grade_small = 8;  // graded block sizes along the schedule, in 1/16 rounds of work to go
-  bool sched_force = false;    // tests: schedule even where it cannot pay, grade even short lists (TIM_ATTN_SCHED_FORCE=1)
+  int round_items = 0;         // tim_tuning.round_items: > 0 = a round of the schedule is this many blocks, and even
+                               // launches that fit the chip at once are scheduled (small shapes in tests)
   bool timing_on = false;      // kernel timing for benchmarks (tim_timing_begin / _end)
   int timing_n = 0;
   std::vector<hipEvent_t> ev_start, ev_stop;

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtim.so")
 OK, ERR_INVALID_ARG, ERR_BAD_TREE, ERR_OOM_PAGES, ERR_HIP, ERR_SEQ_TOO_LONG = 0, -1, -2, -3, -4, -5
 MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, MARK_CLOSE = 1, 2, 3, 4
 OUT_F32, OUT_BF16 = 0, 1
+ATTN_VALU, ATTN_MFMA = 0, 1
 PLAN_HDR, PLAN_TOTALS = 16, 8
 (HDR_SEQ, HDR_N, HDR_N_KEPT, HDR_FIRST_PRUNED, HDR_KEEP_PAGES, HDR_NEED, HDR_PAGE_OFF, HDR_PUSH, HDR_PUSH_OFF,
  HDR_BAD, HDR_EXT, HDR_EXT_OFF, HDR_EXT_TILE_OFF) = range(13)
@@ -22,7 +23,8 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_
 
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_seq_extend", "tim_kv_write", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
-           "tim_attn_schedule", "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end"]
+           "tim_attn_schedule", "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end",
+           "tim_ctx_get_tuning", "tim_ctx_set_tuning"]
 
 
 class tim_config(C.Structure):
@@ -35,6 +37,11 @@ class tim_state(C.Structure):
                                           "status", "node_tok_begin", "node_sub_begin", "node_sub_end",
                                           "node_tok_end", "node_list_order", "n_nodes", "lists_done", "attn_ws")] + \
                [("attn_ws_bytes", C.c_int64), ("keep_mask", C.c_void_p)]
+
+
+class tim_tuning(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("attn_impl", "chunks_per_block", "fill", "grade_big", "grade_small",
+                                         "round_items")]
 
 
 _PLAN_PTRS = ("seq_ids", "cover", "rank", "kept_idx", "new_pos", "delta", "src_slot", "dst_slot", "new_table",
@@ -71,7 +78,9 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_decode_attn_masked": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_prune_mask": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
         "tim_extend_attn": (C.c_int, [p, i32, C.POINTER(tim_plan), p, p, i32, f32, i32, p]),
-        "tim_pool_stats": (C.c_int, [p, p, p]),
+        "tim_pool_stats": (C.c_int, [p, p, p, p]),
+        "tim_ctx_get_tuning": (C.c_int, [p, C.POINTER(tim_tuning)]),
+        "tim_ctx_set_tuning": (C.c_int, [p, C.POINTER(tim_tuning)]),
         "tim_status": (C.c_int, [p, p]),
         "tim_timing_begin": (C.c_int, [p, i32]),
         "tim_timing_end": (C.c_int, [p, C.POINTER(f32), C.POINTER(i32)]),
@@ -275,10 +284,27 @@ class Context:
         _check(lib().tim_extend_attn(self.handle, layer, C.byref(plan.c), _ptr(q_ext), _ptr(out_ext),
                                      q_ext.shape[0], sm_scale, od, _stream()), "tim_extend_attn")
 
-    def tim_pool_stats(self) -> torch.Tensor:
-        out = torch.zeros(2, dtype=torch.int32, device=self.seq_len.device)
-        _check(lib().tim_pool_stats(self.handle, _ptr(out), _stream()), "tim_pool_stats")
+    def tim_pool_stats(self, check_duplicates: bool = True) -> torch.Tensor:
+        """int32 [4]: free pages, page-table entries in use, pages the lengths call for, duplicate flag."""
+        out = torch.empty(4, dtype=torch.int32, device=self.seq_len.device)
+        scratch = torch.empty(self.cfg.num_pages, dtype=torch.int32, device=self.seq_len.device) if check_duplicates else None
+        _check(lib().tim_pool_stats(self.handle, _ptr(out), _ptr(scratch) if check_duplicates else None, _stream()),
+               "tim_pool_stats")
         return out
+
+    def tim_ctx_get_tuning(self) -> tim_tuning:
+        t = tim_tuning()
+        _check(lib().tim_ctx_get_tuning(self.handle, C.byref(t)), "tim_ctx_get_tuning")
+        return t
+
+    def tim_ctx_set_tuning(self, **fields):
+        """Reads the current tuning, replaces the named fields, installs the result."""
+        t = self.tim_ctx_get_tuning()
+        for k, v in fields.items():
+            if k not in dict(tim_tuning._fields_):
+                raise KeyError(k)
+            setattr(t, k, v)
+        _check(lib().tim_ctx_set_tuning(self.handle, C.byref(t)), "tim_ctx_set_tuning")
 
     def tim_status(self) -> int:
         return lib().tim_status(self.handle, _stream())

@@ -1,12 +1,7 @@
 """Adapter that lets the shared harness drive the GPU library with numpy inputs and
 read its state back as numpy.  Marshalling only."""
-import os
-
 import numpy as np
 import torch
-
-# the library leaves small launches unscheduled; the tests' shapes are small and must still reach that path
-os.environ.setdefault("TIM_ATTN_SCHED_FORCE", "1")
 
 from paper_2507_16784_amd import tim
 from paper_2507_16784_amd.workload import tensors
@@ -30,12 +25,15 @@ class GpuPlanView:
 
 
 class GpuRuntime:
-    def __init__(self, cfg, threshold, max_flush_seqs=None):
-        """cfg: an oracle-style Config dataclass (plain fields only)."""
+    def __init__(self, cfg, threshold, max_flush_seqs=None, tuning=None):
+        """cfg: an oracle-style Config dataclass (plain fields only).  tuning: fields of tim_tuning; by default
+        a schedule round of four blocks, because the library leaves launches that fit the chip at once
+        unscheduled and the tests' small shapes must still reach the scheduled path and all its block sizes."""
         self.cfg = cfg
         self.threshold = threshold
         self.ctx = tim.Context(cfg.layers, cfg.q_heads, cfg.kv_heads, cfg.num_pages, cfg.max_batch,
                                cfg.max_pages_per_seq, cfg.max_nodes, cfg.head_dim, cfg.page_size, cfg.rope_base)
+        self.ctx.tim_ctx_set_tuning(**(dict(round_items=4) if tuning is None else tuning))
         self.plan = tim.Plan(self.ctx.cfg, max_flush_seqs or cfg.max_batch)
         self.dev = self.ctx.seq_len.device
         self.max_len_hint = 0

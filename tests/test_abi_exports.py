@@ -44,4 +44,19 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.tim_attn_schedule(h, 0, None) == tim.ERR_INVALID_ARG
     # partials [batch][q_heads][128 slots][128 + 2] fp32, then the schedule: 4 words, 4 per (sequence, slot), 1 per sequence
     assert lib.tim_attn_ws_bytes(ctypes.byref(ok)) == 1 * 8 * 128 * 130 * 4 + (4 + (4 * 128 + 1) * 1) * 4
+    # launch-shape tuning is a host object: defaults, a round trip, and refused values
+    t = tim.tim_tuning()
+    assert lib.tim_ctx_get_tuning(h, ctypes.byref(t)) == tim.OK
+    assert (t.attn_impl, t.chunks_per_block, t.fill, t.grade_big, t.grade_small, t.round_items) == (tim.ATTN_MFMA, 6, 2, 32, 8, 0)
+    t.chunks_per_block, t.round_items = 3, 4
+    assert lib.tim_ctx_set_tuning(h, ctypes.byref(t)) == tim.OK
+    t2 = tim.tim_tuning()
+    assert lib.tim_ctx_get_tuning(h, ctypes.byref(t2)) == tim.OK and (t2.chunks_per_block, t2.round_items) == (3, 4)
+    for field, bad_value in (("attn_impl", 2), ("chunks_per_block", 0), ("chunks_per_block", 65), ("fill", 0),
+                             ("grade_small", 33), ("grade_small", -1), ("round_items", -1)):
+        t3 = tim.tim_tuning()
+        lib.tim_ctx_get_tuning(h, ctypes.byref(t3))
+        setattr(t3, field, bad_value)
+        assert lib.tim_ctx_set_tuning(h, ctypes.byref(t3)) == tim.ERR_INVALID_ARG, field
+    assert lib.tim_ctx_get_tuning(h, ctypes.byref(t3)) == tim.OK and t3.chunks_per_block == 3     # refused: unchanged
     assert lib.tim_ctx_destroy(h) == tim.OK

@@ -36,14 +36,13 @@ def _gather(ctx, layer, b):
     return tensors.bits(ctx.k_pool[layer, pages, :, rows].cpu()), tensors.bits(ctx.v_pool[layer, pages, :, rows].cpu())
 
 
-def test_config3_full_size_sampled(monkeypatch):
+def test_config3_full_size_sampled():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import bench
     from paper_2507_16784_amd import tim
     from test_gpu_parity import check_attention, check_plan, check_rotated
     import gpu_backend
-    monkeypatch.setenv("TIM_ATTN_SCHED_FORCE", "0")     # the launch configuration bench.py times, not the small tests' override
 
     gc.collect()
     torch.cuda.empty_cache()
@@ -137,7 +136,7 @@ def test_config3_full_size_sampled(monkeypatch):
                     kb, vb = ko, vo
                 want = attend(bf16.to_f64(tensors.bits(q[b].cpu())), bf16.to_f64(kb), bf16.to_f64(vb), shape.q_scale)
                 check_attention(got[b], want.astype(np.float32))
-                assert np.all(np.abs(got16[b] - want) <= 2e-2 + 1e-2 * np.abs(want))
+                check_attention(got16[b], want.astype(np.float32))          # bf16 output and partials: both gates too
         assert ctx.tim_status() == 0
     del ctx, plan
     gc.collect()
