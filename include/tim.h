@@ -67,7 +67,8 @@ typedef enum {
   TIM_ERR_BAD_TREE = -2,     /* mark or node span outside the sequence / tables */
   TIM_ERR_OOM_PAGES = -3,    /* free stack holds fewer pages than a batch needs */
   TIM_ERR_HIP = -4,          /* a HIP runtime call failed */
-  TIM_ERR_SEQ_TOO_LONG = -5  /* a sequence needs more than max_pages_per_seq pages */
+  TIM_ERR_SEQ_TOO_LONG = -5, /* a sequence needs more than max_pages_per_seq pages */
+  TIM_ERR_TOO_LARGE = -6     /* the configuration exceeds what tim_decode_attn_noalloc's built-in scratch holds */
 } tim_error;
 
 /* Structural marks of the task tree (Sec. 2.1: thought, subtasks, conclusion). */
@@ -172,7 +173,9 @@ int64_t tim_attn_ws_bytes(const tim_config *cfg);
 int tim_ctx_create(tim_ctx **out, const tim_config *cfg);
 int tim_ctx_destroy(tim_ctx *ctx);
 
-/* Attaches the caller's device buffers; all pointers must be non-null. */
+/* Attaches the caller's device buffers; all pointers must be non-null, except keep_mask (see there) and
+ * attn_ws, which may be NULL (with attn_ws_bytes 0) for a caller that only attends through
+ * tim_decode_attn_noalloc; the other attention calls then return TIM_ERR_INVALID_ARG. */
 int tim_bind(tim_ctx *ctx, const tim_state *state);
 
 /*
@@ -353,6 +356,26 @@ int tim_decode_attn_append(tim_ctx *ctx, int32_t layer, const void *q, const voi
  */
 int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan, const void *q_ext, void *out_ext,
                     int32_t n_ext_total, float sm_scale, int32_t out_dtype, tim_stream stream);
+
+/*
+ * tim_decode_attn for callers that cannot allocate a workspace or may not call an allocating routine at
+ * all: code being captured into a HIP graph, tight serving loops, harnesses that forbid allocation.
+ * Same arguments, same result (up to summation order) as tim_decode_attn, but the partial results of split
+ * sequences pass through a device array of TIM_NOALLOC_SCRATCH_BYTES that is part of the library's own
+ * image (each GPU the library runs on holds one copy until the process ends) instead of
+ * tim_state.attn_ws, which is not touched and may be NULL.  The call allocates and frees nothing, and
+ * launches kernels only.  It never uses a schedule (tim_attn_schedule lives in attn_ws).
+ * Limit: one slot's partials, max_batch * q_heads * 520 bytes, must fit the array, else
+ * TIM_ERR_TOO_LARGE is returned and nothing is launched (32,263 (sequence, head) pairs: a batch of
+ * 1,008 at 32 query heads).  Within the limit the launch uses as many slots per sequence as fit
+ * (15 at batch 64 with 32 heads); longer sequences get larger blocks, never a wrong result.
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two streams, two
+ * contexts, two threads) race on it and must be serialised by the caller.  Nothing in it needs
+ * clearing between calls: every record a call reads, it has written first.
+ */
+#define TIM_NOALLOC_SCRATCH_BYTES (16 << 20)
+int tim_decode_attn_noalloc(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
+                            int32_t max_seq_len, tim_stream stream);
 
 /*
  * In-forward variant (Sec. 3.1 mentions it and rejects it as slower; Sec. 4.3 plots it as a

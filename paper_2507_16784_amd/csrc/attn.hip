@@ -17,6 +17,8 @@
 // merged once at the end (log-sum-exp algebra), then a small kernel merges the slots.
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 #include "tim_internal.h"
 
 #define AT_THREADS 256
@@ -781,7 +783,7 @@ tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sch
 }
 
 extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream) {
-  if (!ctx || !ctx->bound || max_seq_len < 0) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || max_seq_len < 0 || !ctx->st.attn_ws) return TIM_ERR_INVALID_ARG;
   at_shape(ctx, max_seq_len, &ctx->sched_cpb, &ctx->sched_slots);
   // Nothing to gain when every block of the bound's grid is resident at once (idle blocks then cost nothing,
   // and on configuration 4, 117 MB per launch, the list's order paired blocks on CUs worse than the grid's:
@@ -862,21 +864,76 @@ extern "C" int tim_timing_end(tim_ctx *ctx, float *ms_out, int32_t *n_out) {
   return rc;
 }
 
+// ---- split partials in memory the library itself holds -----------------------------------------------
+// For callers that cannot hand over a workspace they allocated (code under graph capture, serving loops
+// and harnesses that forbid allocation): the partial results of tim_decode_attn_noalloc pass through this
+// file-scope device array instead of tim_state.attn_ws.  Each GPU the library runs on holds its own copy
+// of the array, at its own address, until the process ends.  In host code the array's name is only a
+// handle: the address a kernel may use comes from hipGetSymbolAddress, asked once per device with that
+// device current, and is kept per device.
+static __device__ __align__(256) unsigned char tim_noalloc_scratch[TIM_NOALLOC_SCRATCH_BYTES];
+
+#define AT_MAX_DEVICES 64
+static std::mutex at_scratch_mutex;
+static void *at_scratch_ptr[AT_MAX_DEVICES];  // per device, nullptr = not asked yet
+
+static int at_noalloc_scratch(float **out) {
+  int dev = -1;
+  TIM_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= AT_MAX_DEVICES) return TIM_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(at_scratch_mutex);
+  if (!at_scratch_ptr[dev]) {
+    void *p = nullptr;
+    TIM_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(tim_noalloc_scratch)));
+    if (!p) return TIM_ERR_HIP;
+    at_scratch_ptr[dev] = p;
+  }
+  *out = reinterpret_cast<float *>(at_scratch_ptr[dev]);
+  return TIM_OK;
+}
+
+// Called by tim_ctx_create with the context's device current, so that a first attention call made under graph
+// capture finds the address already known.  Without a usable device (a host-only build check) it does nothing
+// and the entry point asks on its first call.
+void tim_noalloc_scratch_init() {
+  float *unused = nullptr;
+  (void)at_noalloc_scratch(&unused);
+  (void)hipGetLastError();  // a failure here is not the caller's: the entry point will report it if it persists
+}
+
 static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                      int32_t max_seq_len, tim_stream stream, bool masked, const void *k_new = nullptr,
-                     const void *v_new = nullptr) {
-  if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers ||
+                     const void *v_new = nullptr, bool own_scratch = false) {
+  if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers || (!own_scratch && !ctx->st.attn_ws) ||
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask) ||
       (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
     return TIM_ERR_INVALID_ARG;
   const tim_config &cfg = ctx->cfg;
   int cpb, slots;
   AttnWs ws;
-  ws.ml = ctx->st.attn_ws;
-  ws.o = ws.ml + (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * 2;
+  ws.ml = ws.o = nullptr;
   ws.sched = nullptr;
+  if (!own_scratch) {
+    ws.ml = ctx->st.attn_ws;
+    ws.o = ws.ml + (int64_t)cfg.max_batch * cfg.q_heads * AT_MAX_SLOTS * 2;
+  }
   dim3 grid;
-  if (ctx->sched_valid) {  // the schedule's shape, not this call's bound: the merge must see the same slots
+  if (own_scratch) {
+    // Unscheduled (a schedule lives in the caller's workspace), and with as many slots as the library's own
+    // array holds partials for: records [B][Hkv][slots][4 heads] of (m, l), then of o[128], all fp32-sized.
+    // Fewer slots than the bound asks for only mean larger blocks: a block strides over its sequence's chunks.
+    const int64_t per_slot = (int64_t)cfg.max_batch * cfg.q_heads * (TIM_D + 2) * (int64_t)sizeof(float);
+    if (per_slot > (int64_t)TIM_NOALLOC_SCRATCH_BYTES) return TIM_ERR_TOO_LARGE;
+    float *base = nullptr;
+    const int rc = at_noalloc_scratch(&base);
+    if (rc != TIM_OK) return rc;
+    at_shape(ctx, max_seq_len, &cpb, &slots);
+    const int fit = (int)((int64_t)TIM_NOALLOC_SCRATCH_BYTES / per_slot);
+    if (slots > fit) slots = fit;
+    ws.ml = base;
+    ws.o = base + (int64_t)cfg.max_batch * cfg.q_heads * slots * 2;
+    grid = dim3(cfg.max_batch * cfg.kv_heads, slots);
+  } else if (ctx->sched_valid) {  // the schedule's shape, not this call's bound: the merge must see the same slots
     cpb = ctx->sched_cpb;
     slots = ctx->sched_slots;
     ws.sched = reinterpret_cast<const int32_t *>(ctx->st.attn_ws + at_partials_words(cfg));
@@ -911,6 +968,11 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
 extern "C" int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
                                int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
   return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, false);
+}
+
+extern "C" int tim_decode_attn_noalloc(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,
+                                       int32_t out_dtype, int32_t max_seq_len, tim_stream stream) {
+  return at_decode(ctx, layer, q, out, sm_scale, out_dtype, max_seq_len, stream, false, nullptr, nullptr, true);
 }
 
 extern "C" int tim_decode_attn_masked(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale,

@@ -26,6 +26,7 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
     c->n_cu = prop.multiProcessorCount;
+  if (hipGetDevice(&dev) == hipSuccess) tim_noalloc_scratch_init();
   for (int i = 0; i < TIM_D / 2; ++i) c->inv_freq[i] = std::pow((double)cfg->rope_base, -2.0 * i / TIM_D);
   *out = c;
   return TIM_OK;
@@ -67,9 +68,10 @@ extern "C" int tim_bind(tim_ctx *ctx, const tim_state *s) {
   if (!ctx || !s) return TIM_ERR_INVALID_ARG;
   if (!s->k_pool || !s->v_pool || !s->page_table || !s->seq_len || !s->free_stack || !s->free_top || !s->status ||
       !s->node_tok_begin || !s->node_sub_begin || !s->node_sub_end || !s->node_tok_end || !s->node_list_order ||
-      !s->n_nodes || !s->lists_done || !s->attn_ws)
+      !s->n_nodes || !s->lists_done)
     return TIM_ERR_INVALID_ARG;
-  if (s->attn_ws_bytes < tim_attn_ws_bytes(&ctx->cfg)) return TIM_ERR_INVALID_ARG;
+  // the workspace is optional (tim_decode_attn_noalloc needs none); if given it must be large enough
+  if (s->attn_ws && s->attn_ws_bytes < tim_attn_ws_bytes(&ctx->cfg)) return TIM_ERR_INVALID_ARG;
   ctx->st = *s;
   ctx->bound = true;
   ctx->sched_valid = false;

@@ -41,6 +41,9 @@ struct tim_ctx {
 
 #define TIM_LAUNCH_CHECK() TIM_HIP_CHECK(hipGetLastError())
 
+// attn.hip: looks up, for the current device, the address of the array tim_decode_attn_noalloc uses
+void tim_noalloc_scratch_init();
+
 static inline hipStream_t tim_hs(tim_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
 // words per sequence of the visibility mask: one bit per logical token

@@ -12,7 +12,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtim.so")
 
-OK, ERR_INVALID_ARG, ERR_BAD_TREE, ERR_OOM_PAGES, ERR_HIP, ERR_SEQ_TOO_LONG = 0, -1, -2, -3, -4, -5
+OK, ERR_INVALID_ARG, ERR_BAD_TREE, ERR_OOM_PAGES, ERR_HIP, ERR_SEQ_TOO_LONG, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+NOALLOC_SCRATCH_BYTES = 16 << 20
 MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, MARK_CLOSE = 1, 2, 3, 4
 OUT_F32, OUT_BF16 = 0, 1
 ATTN_VALU, ATTN_MFMA = 0, 1
@@ -24,7 +25,7 @@ TOT_OK, TOT_NEED, TOT_PUSH, TOT_TOP_AFTER_POP, TOT_TOP_BEFORE, TOT_EXT, TOT_EXT_
 EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind", "tim_pool_reset", "tim_tree_mark",
            "tim_seq_advance", "tim_seq_extend", "tim_kv_write", "tim_kv_append", "tim_prune_plan", "tim_kv_compact", "tim_plan_commit",
            "tim_attn_schedule", "tim_decode_attn", "tim_decode_attn_append", "tim_decode_attn_masked", "tim_prune_mask", "tim_extend_attn", "tim_pool_stats", "tim_status", "tim_timing_begin", "tim_timing_end",
-           "tim_ctx_get_tuning", "tim_ctx_set_tuning"]
+           "tim_ctx_get_tuning", "tim_ctx_set_tuning", "tim_decode_attn_noalloc"]
 
 
 class tim_config(C.Structure):
@@ -74,6 +75,7 @@ def load_library(path: str = LIB_PATH) -> C.CDLL:
         "tim_plan_commit": (C.c_int, [p, C.POINTER(tim_plan), p]),
         "tim_attn_schedule": (C.c_int, [p, i32, p]),
         "tim_decode_attn": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
+        "tim_decode_attn_noalloc": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_decode_attn_append": (C.c_int, [p, i32, p, p, p, p, f32, i32, i32, p]),
         "tim_decode_attn_masked": (C.c_int, [p, i32, p, p, f32, i32, i32, p]),
         "tim_prune_mask": (C.c_int, [p, p, i32, i32, C.POINTER(tim_plan), p]),
@@ -147,7 +149,7 @@ class Context:
     """One decoding context: owns the torch device buffers of tim_state and the tim_ctx handle."""
 
     def __init__(self, layers, q_heads, kv_heads, num_pages, max_batch, max_pages_per_seq, max_nodes,
-                 head_dim=128, page_size=16, rope_base=1.0e6, device="cuda", pools=None):
+                 head_dim=128, page_size=16, rope_base=1.0e6, device="cuda", pools=None, workspace=True):
         self.cfg = tim_config(layers, q_heads, kv_heads, head_dim, page_size, num_pages, max_batch,
                               max_pages_per_seq, max_nodes, rope_base)
         self.handle = C.c_void_p()
@@ -173,13 +175,14 @@ class Context:
         self.n_nodes = torch.zeros(max_batch, **i32)
         self.lists_done = torch.zeros(max_batch, **i32)
         self.keep_mask = torch.full((max_batch, (max_pages_per_seq * page_size + 31) // 32), -1, **i32)  # all bits set
-        ws_bytes = lib().tim_attn_ws_bytes(C.byref(self.cfg))
-        self.attn_ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=device)
+        ws_bytes = lib().tim_attn_ws_bytes(C.byref(self.cfg)) if workspace else 0
+        self.attn_ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=device) if workspace else None
         self.state = tim_state(
             **{n: getattr(self, n).data_ptr() for n in ("k_pool", "v_pool", "page_table", "seq_len", "free_stack",
                                                         "free_top", "status", "node_tok_begin", "node_sub_begin",
                                                         "node_sub_end", "node_tok_end", "node_list_order", "n_nodes",
-                                                        "lists_done", "attn_ws")},
+                                                        "lists_done")},
+            attn_ws=self.attn_ws.data_ptr() if workspace else None,
             attn_ws_bytes=ws_bytes, keep_mask=self.keep_mask.data_ptr())
         _check(lib().tim_bind(self.handle, C.byref(self.state)), "tim_bind")
         self.tim_pool_reset()
@@ -248,6 +251,14 @@ class Context:
         od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
         _check(lib().tim_decode_attn(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len, _stream()),
                "tim_decode_attn")
+
+    def tim_decode_attn_noalloc(self, layer: int, q: torch.Tensor, out: torch.Tensor, sm_scale: float, max_seq_len: int = 0):
+        assert q.dtype == torch.bfloat16 and q.is_cuda and q.is_contiguous()
+        assert tuple(q.shape) == (self.cfg.max_batch, self.cfg.q_heads, self.cfg.head_dim) == tuple(out.shape)
+        assert out.is_cuda and out.is_contiguous() and out.dtype in (torch.float32, torch.bfloat16)
+        od = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+        _check(lib().tim_decode_attn_noalloc(self.handle, layer, _ptr(q), _ptr(out), sm_scale, od, max_seq_len,
+                                             _stream()), "tim_decode_attn_noalloc")
 
     def tim_decode_attn_append(self, layer: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
                                out: torch.Tensor, sm_scale: float, max_seq_len: int = 0):
