@@ -28,16 +28,47 @@ HBM_PEAK_GBPS = 8000.0
 KV_BYTES_PER_TOKEN_LAYER = 4096          # K + V rows of 8 KV heads x 128 dims, bf16
 
 
+TRAFFIC_FILE = "profiles/attn_mfma_config3_hbm_traffic.txt"
+
+
 def stored_traffic(batch, steps, seed):
-    """HBM bytes per attention launch from the committed rocprofv3 counter runs; they were taken on
-    the default workload, so any other workload reports null."""
-    path = os.path.join(ROOT, "profiles", "attn_mfma_config3_hbm_traffic.txt")
+    """HBM bytes per attention launch from the committed rocprofv3 counter runs (two separate --pmc runs of
+    this same command; counters cannot be read from inside the run).  They were taken on the default
+    workload, so any other workload reports null.  Returns (bytes, label of where the figure comes from)."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     if (batch, steps, seed) != (64, 256, 1000) or not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         if line.startswith("attn_partial_mfma_traffic_bytes_per_launch"):
-            return float(line.split("=")[1])
-    return None
+            return float(line.split("=")[1]), (TRAFFIC_FILE + ": rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
+                                               "(batch 64, 256 steps, seed 1000), stored with the kernel they measured; "
+                                               "not re-measured in this run")
+    return None, None
+
+
+def gpu_clock_state():
+    """Shader / memory clock levels and the performance level as the driver's sysfs files show them
+    (the line marked '*' is the level in use); None where the file cannot be read."""
+    import glob
+    out = {}
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        if not os.path.exists(os.path.join(card, "pp_dpm_sclk")):
+            continue
+        def cur(name):
+            try:
+                lines = open(os.path.join(card, name)).read().split("\n")
+            except OSError:
+                return None
+            star = [l for l in lines if l.strip().endswith("*")]
+            return (star[0].split(":")[1].strip(" *") if star else None)
+        def whole(name):
+            try:
+                return open(os.path.join(card, name)).read().strip()
+            except OSError:
+                return None
+        out = {"sclk": cur("pp_dpm_sclk"), "mclk": cur("pp_dpm_mclk"), "performance_level": whole("power_dpm_force_performance_level")}
+        break
+    return out or None
 
 
 def log(*a):
@@ -154,11 +185,12 @@ def cpu_baseline(shape, seed):
     import harness
     from oracle.runtime import OracleRuntime
     from paper_2507_16784_amd.workload import configs
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    cores = len(os.sched_getaffinity(0))             # cores this process may run on
+    try:                                            # the oracle is single-threaded Python around numpy; numpy's BLAS
+        from threadpoolctl import threadpool_info   # may use this many threads inside a matrix-vector product
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        threads = 1
+        blas_threads = 1
     nseq, before, after = 32, 3, 12
     _, wl = configs.config3(batch=nseq, steps=before + after, seed=seed, stride=0, cadence=10**6)
     cfg = harness.make_config(wl, layers=1, q_heads=shape.q_heads, kv_heads=shape.kv_heads, headroom_pages=12000)
@@ -180,7 +212,7 @@ def cpu_baseline(shape, seed):
         rt.decode_attn(0, q[0], shape.q_scale)
         t_attn += time.perf_counter() - t0
         live_tokens += int(rt.seq_len.sum())
-    return dict(t_event_seq_layer=t_event, t_attn_token_layer=t_attn / live_tokens, threads=threads,
+    return dict(t_event_seq_layer=t_event, t_attn_token_layer=t_attn / live_tokens, cores=cores, blas_threads=blas_threads,
                 seconds=round(t_attn + t_event * nseq, 1),
                 sample=f"{nseq} sequences x 1 layer of configuration 3: {before} decode steps before their big flush, "
                        f"the flush, {after} decode steps after")
@@ -445,6 +477,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the K-step window is timed this many times from the same starting state; value is the median")
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--layers-alloc", type=int, default=0, help="debug: allocate fewer layer pools and alias them")
     ap.add_argument("--seed", type=int, default=1000)
@@ -560,13 +594,23 @@ def main():
         torch.cuda.synchronize()
     for n, t in initial.items():                    # rewind the integer state; K/V content stays random
         getattr(ctx, n).copy_(t)
-    # pass A: the timed region proper, exactly K steps, nothing but the path's own calls
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, None, graph=graph)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    assert ctx.tim_status() == 0
+    # pass A: the timed region proper, exactly K steps, nothing but the path's own calls; repeated from the same
+    # integer state (the K/V content a flush has moved stays random numbers); the median repeat is reported
+    clocks_before = gpu_clock_state()
+    dts = []
+    for r in range(max(1, args.repeats)):
+        if r:
+            for n, t in initial.items():
+                getattr(ctx, n).copy_(t)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(torch, tim, ctx, plan, shape, wl, staged, args.steps, shape.layers, None, graph=graph)
+        torch.cuda.synchronize()
+        dts.append(time.perf_counter() - t0)
+        assert ctx.tim_status() == 0
+        log(f"[bench] repeat {r}: {args.steps / dts[-1]:.3f} steps/s")
+    clocks_after = gpu_clock_state()
+    dt = float(np.median(dts))
     # pass B: the same K steps again from the same state, instrumented: HIP events ride on the dispatch
     # of every attention main kernel (on the launch stream), lengths and plan headers are logged
     for n, t in initial.items():
@@ -608,10 +652,14 @@ def main():
     steady = lens.max(axis=1) < 8192                                 # steps after every big flush
     steady_launch = np.repeat(steady, shape.layers)
     steps_per_s = args.steps / dt
+    traffic, traffic_source = (stored_traffic(B, args.steps, args.seed)
+                               if (args.page_size == 16 and args.workload == "config3") else (None, None))
     res = {
         "metric": METRIC, "value": round(steps_per_s, 3), "unit": "decode steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * dt / args.steps, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "repeats": {"n": len(dts), "value_is": "median", "steps_per_s": [round(args.steps / x, 3) for x in dts],
+                    "min": round(args.steps / max(dts), 3), "max": round(args.steps / min(dts), 3)},
         "tokens_per_s": round(steps_per_s * B, 1), "ms_per_step_instrumented_replay": round(1e3 * dt_instrumented / args.steps, 4),
         "achieved_hbm_gbps": round(total_bytes / dt / 1e9, 1),
         "hbm_frac_of_peak": round(total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 4),
@@ -623,12 +671,12 @@ def main():
                    "moved_tokens": moved, "flush_calls": len(record["hdr"]),
                    "pages_popped_by_flushes": pages_popped, "pages_pushed_by_flushes": pages_pushed,
                    "max_position_shift": max_shift, "mean_live_tokens_per_seq": round(float(lens.mean()), 1),
-                   "bytes_per_step_GB": round(total_bytes / args.steps / 1e9, 3)},
+                   "bytes_per_step_GB": round(total_bytes / args.steps / 1e9, 3),
+                   "gpu_clocks_before": clocks_before, "gpu_clocks_after": clocks_after},
         "roofline": {"bound": "hbm", "kernel": "tim_attn_partial_mfma_kernel",
                      "achieved": round(float(achieved), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(float(achieved) / HBM_PEAK_GBPS, 4),
-                     "traffic": stored_traffic(B, args.steps, args.seed)
-                     if (args.page_size == 16 and args.workload == "config3") else None,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "launches": int(attn_ms.size), "avg_launch_us": round(float(attn_ms.mean()) * 1e3, 2),
                      "avg_bytes_per_launch": round(float(attn_bytes_launch.mean()), 1)},
     }
@@ -646,8 +694,8 @@ def main():
         big_per_step = len(big_ratios) / args.steps
         t_step = (float(lens.sum(axis=1).mean()) * shape.layers * cb["t_attn_token_layer"]
                   + big_per_step * shape.layers * cb["t_event_seq_layer"])
-        res["cpu_baseline"] = {"value": round(1.0 / t_step, 6), "unit": "decode steps/s", "cores": cb["threads"],
-                               "kind": "oracle", "sample_seconds": cb["seconds"], "sample": cb["sample"] +
+        res["cpu_baseline"] = {"value": round(1.0 / t_step, 6), "unit": "decode steps/s", "cores": cb["cores"],
+                               "blas_threads": cb["blas_threads"], "kind": "oracle", "sample_seconds": cb["seconds"], "sample": cb["sample"] +
                                "; per-token-layer and per-flush-layer times scaled to the timed window (extrapolated)"}
     print(json.dumps(res), flush=True)
 
