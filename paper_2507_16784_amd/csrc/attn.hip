@@ -105,7 +105,7 @@ __device__ __forceinline__ void at_store_through(float4 *p, const float4 &v) {
 // last block to finish, behind an agent-scope counter, was measured and rejected: the
 // release/acquire fences it needs write back and invalidate the XCD's whole L2 per block
 // and cost 6x the kernel's run time.)
-template <int NS, bool OUT_BF16>
+template <int NS, int NT, bool OUT_BF16>  // NS states in LDS, NT threads in the block
 __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &ws, void *out, const float *red_m,
                                           const float *red_l, const float *red_o, int b, int kvh, int slot, int slots,
                                           int used) {
@@ -145,19 +145,20 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
   };
   if (OUT_BF16 && used > 1) {
     // bf16 partial: thread -> head tid / 64, dims 2 (tid % 64) and the next one, one 32-bit word
-    static_assert(AT_THREADS == TIM_G * TIM_D / 2, "one pair of dims per thread");
-    const int h = tid >> 6, d0 = 2 * (tid & 63);
-    float mx, lt, mx1, lt1;
-    const float o0 = merged(h, d0, mx, lt), o1 = merged(h, d0 + 1, mx1, lt1);
-    const float inv = lt > 0.f ? 1.f / lt : 0.f;  // (a slot whose tokens are all hidden has l = 0)
-    const int64_t pi = (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * TIM_G + h;  // a block's four rows are contiguous
-    at_store_through(reinterpret_cast<uint32_t *>(ws.o) + (pi * TIM_D + d0) / 2, at_pack_bf16(o0 * inv, o1 * inv));
-    if (tid == 0) store_ml();
+    static_assert(NT >= TIM_G * TIM_D / 2, "one pair of dims per thread");
+    if (tid < TIM_G * TIM_D / 2) {
+      const int h = tid >> 6, d0 = 2 * (tid & 63);
+      float mx, lt, mx1, lt1;
+      const float o0 = merged(h, d0, mx, lt), o1 = merged(h, d0 + 1, mx1, lt1);
+      const float inv = lt > 0.f ? 1.f / lt : 0.f;  // (a slot whose tokens are all hidden has l = 0)
+      const int64_t pi = (((int64_t)b * cfg.kv_heads + kvh) * slots + slot) * TIM_G + h;  // a block's four rows are contiguous
+      at_store_through(reinterpret_cast<uint32_t *>(ws.o) + (pi * TIM_D + d0) / 2, at_pack_bf16(o0 * inv, o1 * inv));
+      if (tid == 0) store_ml();
+    }
     return;
   }
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int idx = tid + r * AT_THREADS;  // 0..511 = (h, dim)
+  for (int idx = tid; idx < TIM_G * TIM_D; idx += NT) {  // idx = (h, dim)
     const int h = idx >> 7, dim = idx & 127, hq = kvh * TIM_G + h;
     float mx, lt;
     const float ot = merged(h, dim, mx, lt);
@@ -175,7 +176,7 @@ __device__ __forceinline__ void at_finish(const tim_config &cfg, const AttnWs &w
 // A sequence with no tokens has no block that computes; slot 0 defines its output as zero.
 template <bool OUT_BF16>
 __device__ __forceinline__ void at_empty_out(const tim_config &cfg, void *out, int b, int kvh) {
-  for (int idx = threadIdx.x; idx < TIM_G * TIM_D; idx += AT_THREADS)
+  for (int idx = threadIdx.x; idx < TIM_G * TIM_D; idx += blockDim.x)
     at_store_out<OUT_BF16>(out, ((int64_t)b * cfg.q_heads + kvh * TIM_G) * TIM_D + idx, 0.f);
 }
 
@@ -355,7 +356,7 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
   }
   __syncthreads();
   at_check_live(st, ws, b, n);
-  at_finish<AT_WAVES * 4, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
+  at_finish<AT_WAVES * 4, AT_THREADS, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
                                     used);
 }
 
@@ -382,30 +383,37 @@ tim_attn_partial_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, cons
 
 #define AT_LAZY_MAX 8.0f
 
-template <bool OUT_BF16, bool MASKED, bool PS1>
-__global__ void __launch_bounds__(AT_THREADS, AT_BLOCKS_PER_CU)
+// WAVES = waves per block (4, 6 or 12; the host picks it so that a CU holds about twelve waves whatever the
+// number of blocks, see at_shape).  The pairs of pages of a sequence are dealt round-robin over all the waves
+// of all its blocks: unit u = slot * WAVES + wave takes pairs u, u + U, u + 2U, ... with U = used * WAVES, so
+// the waves' shares differ by at most one pair whatever the length.
+template <bool OUT_BF16, bool MASKED, bool PS1, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES, 12 / WAVES)
 tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer, const uint4 *__restrict__ q,
                              void *__restrict__ out, float scale_log2, int cpb, int slots,
                              const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new) {
-  __shared__ float red_m[AT_WAVES][TIM_G];
-  __shared__ float red_l[AT_WAVES][TIM_G];
-  __shared__ float red_o[AT_WAVES][TIM_G][TIM_D];
+  __shared__ float red_m[WAVES][TIM_G];
+  __shared__ float red_l[WAVES][TIM_G];
+  __shared__ float red_o[WAVES][TIM_G][TIM_D];
 
   AtWork wk;
   if (!at_take_work<OUT_BF16>(cfg, st, ws, out, slots, cpb, wk)) return;
   const int b = wk.b, kvh = wk.kvh, slot = wk.slot, n = wk.n, used = wk.used;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
-  // Page ids run one chunk ahead of the tiles they name, so that no tile load waits for a page-id load
-  // first.  lane i of the result holds page chunk * 16 + w * 4 + i % 4.  Entries past the sequence's
-  // end are read (the index is clamped to the table's row) but never used.
-  const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
-  auto load_pids = [&](int chunk_) {
-    return ptab[min(chunk_ * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE + (lane & (AT_PAGES_PER_WAVE - 1)), cfg.max_pages_per_seq - 1)];
-  };
-  int next_pid = 0;
-  if (!PS1) next_pid = load_pids(slot);
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
-  const int nchunks = (n_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
+  const int n_pairs = (n_pages + 1) >> 1;
+  const int unit = slot * WAVES + w, stride = used * WAVES;  // this wave's pairs: unit, unit + stride, ...
+  // Page ids run ahead of the tiles they name, so that no tile load waits for a page-id load first: lane i of
+  // one load holds page 2 * (unit + (k0 + i / 2) * stride) + i % 2, the ids of 32 of the wave's pairs, and the next
+  // 32 are requested when these come into use.  Entries past the sequence's end are read (the index is
+  // clamped to the table's row) but never used.
+  const int32_t *ptab = st.page_table + (int64_t)b * cfg.max_pages_per_seq;
+  auto load_pids = [&](int k0) {
+    const int64_t pg_ = 2 * ((int64_t)unit + (int64_t)(k0 + (lane >> 1)) * stride) + (lane & 1);
+    return ptab[(int)min(pg_, (int64_t)cfg.max_pages_per_seq - 1)];
+  };
+  int my_pid = 0, next_pid = 0;
+  if (!PS1) next_pid = load_pids(0);
 
   // B operand of the score product: Q^T, head j (zero for j >= 4), dims 32s + 8g .. +8
   uint4 qb[4];
@@ -426,187 +434,184 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   const int64_t layer_base = (int64_t)layer * cfg.num_pages;
 
   // Page size 1: a "page" below is a run of 16 tokens and every row has its own page id.  The ids of a pair's
-  // 32 tokens are one load (lane l holds token 32 (pg / 2) + l % 32), requested one pair ahead like the page
+  // 32 tokens are one load (lane l holds token 32 * pair + l % 32), requested one pair ahead like the page
   // ids above, and handed to the lanes that need them by cross-lane reads.
-  auto load_row_ids = [&](int pg_) { return ptab[min(pg_ * TIM_PS + (lane & 31), n - 1)]; };
+  auto load_row_ids = [&](int pr_) { return ptab[(int)min((int64_t)pr_ * (2 * TIM_PS) + (lane & 31), (int64_t)n - 1)]; };
   int next_ids = 0;
-  if (PS1) next_ids = load_row_ids(slot * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE);
+  if (PS1) next_ids = load_row_ids(min(unit, n_pairs - 1));
 
-  for (int chunk = slot; chunk < nchunks; chunk += used) {
-    const int pg0 = chunk * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE;
-    const int pg1 = min(pg0 + AT_PAGES_PER_WAVE, n_pages);
-    // the wave's page ids of this chunk: lane i holds page pg0 + i % 4; the next chunk's are requested now.
-    const int my_pid = next_pid;
-    if (!PS1) next_pid = load_pids(chunk + used);
-    for (int pg = pg0; pg < pg1; pg += 2) {
-      const bool has_b = pg + 1 < pg1;
-      int my_ids = next_ids;
-      if (PS1) next_ids = load_row_ids(pg + 2 < pg1 ? pg + 2 : (chunk + used) * AT_CHUNK_PAGES + w * AT_PAGES_PER_WAVE);
-      // in-forward variant: visibility of the pair's 32 tokens (pairs start at even pages);
-      // a pair without a visible token is not read at all
-      uint32_t vis = 0xffffffffu;
-      if (MASKED) {
-        vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * tim_mask_words(cfg) + (pg >> 1)]);
-        if (vis == 0) continue;
+  int k = 0;
+  for (int pr = unit; pr < n_pairs; pr += stride, ++k) {
+    const int pg = 2 * pr;
+    const bool has_b = pg + 1 < n_pages;
+    if (!PS1 && (k & 31) == 0) {  // the ids of this and the next 31 pairs arrive; those of the 32 after them are requested
+      my_pid = next_pid;
+      if ((int64_t)pr + 32 * (int64_t)stride < n_pairs) next_pid = load_pids(k + 32);
+    }
+    int my_ids = next_ids;
+    if (PS1) next_ids = load_row_ids(min(pr + stride, n_pairs - 1));
+    // in-forward variant: visibility of the pair's 32 tokens; a pair without a visible token is not read at all
+    uint32_t vis = 0xffffffffu;
+    if (MASKED) {
+      vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * tim_mask_words(cfg) + pr]);
+      if (vis == 0) continue;
+    }
+    uint4 ka[4], kb[4], va[4], vb[4];
+    int64_t row_a = 0, row_b = 0;  // 16-byte units: start of page A's / page B's tile (page size 1: unused)
+    if (PS1) {
+      // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  K rows are read
+      // in 64-byte pieces by four instructions and need the L1 (ordinary loads; non-temporal ones measured 6 %
+      // slower); a V row is read whole by one instruction: non-temporal, +4 %.
+      if (my_ids < 0 || my_ids >= cfg.num_pages) {  // never dereference a bad page id
+        tim_set_status(st.status, TIM_ERR_INVALID_ARG);
+        my_ids = 0;
       }
-      uint4 ka[4], kb[4], va[4], vb[4];
-      if (PS1) {
-        // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  K rows are read
-        // in 64-byte pieces by four instructions and need the L1 (ordinary loads; non-temporal ones measured 6 %
-        // slower); a V row is read whole by one instruction: non-temporal, +4 %.
-        if (my_ids < 0 || my_ids >= cfg.num_pages) {  // never dereference a bad page id
-          tim_set_status(st.status, TIM_ERR_INVALID_ARG);
-          my_ids = 0;
-        }
-        const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
-        int ids[10];
-        ids[0] = __shfl(my_ids, j, 64);
-        ids[1] = __shfl(my_ids, off_b + j, 64);
+      const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
+      int ids[10];
+      ids[0] = __shfl(my_ids, j, 64);
+      ids[1] = __shfl(my_ids, off_b + j, 64);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          ids[2 + i] = __shfl(my_ids, 4 * g + i, 64);
-          ids[6 + i] = __shfl(my_ids, off_b + 4 * g + i, 64);
-        }
-        const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
-      } else {
-        int phys_a = __builtin_amdgcn_readlane(my_pid, pg - pg0);
-        int phys_b = __builtin_amdgcn_readlane(my_pid, has_b ? pg - pg0 + 1 : pg - pg0);
-        if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
-          tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
-          phys_a = phys_b = 0;
-        }
-        const int64_t tile_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-        const int64_t tile_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + tile_a + j * 16 + 4 * s + g);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + tile_b + j * 16 + 4 * s + g);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + tile_a + (4 * g + i) * 16 + j);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + tile_b + (4 * g + i) * 16 + j);
+      for (int i = 0; i < 4; ++i) {
+        ids[2 + i] = __shfl(my_ids, 4 * g + i, 64);
+        ids[6 + i] = __shfl(my_ids, off_b + 4 * g + i, 64);
       }
+      const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
+    } else {
+      int phys_a = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31));
+      int phys_b = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31) + (has_b ? 1 : 0));
+      if (phys_a < 0 || phys_a >= cfg.num_pages || phys_b < 0 || phys_b >= cfg.num_pages) {
+        tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
+        phys_a = phys_b = 0;
+      }
+      row_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+      row_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + row_a + j * 16 + 4 * s + g);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + row_b + j * 16 + 4 * s + g);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + row_a + (4 * g + i) * 16 + j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + row_b + (4 * g + i) * 16 + j);
+    }
 
-      // fused append: the wave that owns the sequence's last page takes the pending token's
-      // row from the caller's buffers instead of the pool, and stores it into the pool
-      if (k_new != nullptr) {
-        const int last_tok = n - 1, last_pg = last_tok / TIM_PS, row = last_tok % TIM_PS;
-        if (pg == last_pg || (has_b && pg + 1 == last_pg)) {  // uniform for the wave
-          const bool in_b = pg != last_pg;
-          int64_t krow, vrow;  // 16-byte units of the row's start in the pools
-          if (PS1) {
-            int sid = ptab[last_tok];
-            if (sid < 0 || sid >= cfg.num_pages) sid = 0;  // reported by the loads above
-            krow = vrow = ((layer_base + sid) * cfg.kv_heads + kvh) * 16;
-          } else {
-            int phys = __builtin_amdgcn_readlane(my_pid, last_pg - pg0);
-            if (phys < 0 || phys >= cfg.num_pages) phys = 0;
-            krow = vrow = ((layer_base + phys) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16) + row * 16;
+    // fused append: the wave that owns the sequence's last page takes the pending token's
+    // row from the caller's buffers instead of the pool, and stores it into the pool
+    if (k_new != nullptr) {
+      const int last_tok = n - 1, last_pg = last_tok / TIM_PS, row = last_tok % TIM_PS;
+      if (pg == last_pg || (has_b && pg + 1 == last_pg)) {  // uniform for the wave
+        const bool in_b = pg != last_pg;
+        int64_t krow;  // 16-byte units of the row's start in the pools
+        if (PS1) {
+          int sid = ptab[last_tok];
+          if (sid < 0 || sid >= cfg.num_pages) sid = 0;  // reported by the loads above
+          krow = ((layer_base + sid) * cfg.kv_heads + kvh) * 16;
+        } else {
+          krow = (in_b ? row_b : row_a) + row * 16;
+        }
+        const int64_t src = ((int64_t)b * cfg.kv_heads + kvh) * 16;
+        if (j == row) {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint4 x = k_new[src + 4 * s + g];
+            if (in_b) kb[s] = x; else ka[s] = x;
+            const_cast<uint4 *>(kpool)[krow + 4 * s + g] = x;
           }
-          const int64_t src = ((int64_t)b * cfg.kv_heads + kvh) * 16;
-          if (j == row) {
+        }
+        if ((row >> 2) == g) {
+          const uint4 x = v_new[src + j];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-              const uint4 x = k_new[src + 4 * s + g];
-              if (in_b) kb[s] = x; else ka[s] = x;
-              const_cast<uint4 *>(kpool)[krow + 4 * s + g] = x;
+          for (int i = 0; i < 4; ++i)
+            if (i == (row & 3)) {
+              if (in_b) vb[i] = x; else va[i] = x;
             }
-          }
-          if ((row >> 2) == g) {
-            const uint4 x = v_new[src + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (i == (row & 3)) {
-                if (in_b) vb[i] = x; else va[i] = x;
-              }
-            const_cast<uint4 *>(vpool)[vrow + j] = x;
-          }
+          const_cast<uint4 *>(vpool)[krow + j] = x;
         }
       }
+    }
 
-      // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
-      const int left_a = n - pg * TIM_PS;
-      const int left_b = has_b ? n - (pg + 1) * TIM_PS : 0;
-      const bool full = left_b >= TIM_PS && vis == 0xffffffffu;  // then page A is full as well
+    // rows that exist: page A has left_a >= 1 rows, page B left_b (0 if absent)
+    const int left_a = n - pg * TIM_PS;
+    const int left_b = has_b ? n - (pg + 1) * TIM_PS : 0;
+    const bool full = left_b >= TIM_PS && vis == 0xffffffffu;  // then page A is full as well
 
-      at_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    at_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < 4; ++s) sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(ka[s]), at_as_bf16x8(qb[s]), sa, 0, 0, 0);
+    for (int s = 0; s < 4; ++s) sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(ka[s]), at_as_bf16x8(qb[s]), sa, 0, 0, 0);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(kb[s]), at_as_bf16x8(qb[s]), sb, 0, 0, 0);
+    for (int s = 0; s < 4; ++s) sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(kb[s]), at_as_bf16x8(qb[s]), sb, 0, 0, 0);
 
-      float t[8];
-      if (full) {
+    float t[8];
+    if (full) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          t[r] = fmaf(sa[r], scale_log2, lane_bias);
-          t[4 + r] = fmaf(sb[r], scale_log2, lane_bias);
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok_a = 4 * g + r < left_a && ((vis >> (4 * g + r)) & 1u);
-          const bool ok_b = 4 * g + r < left_b && ((vis >> (16 + 4 * g + r)) & 1u);
-          // the select is on the product: a stale row may hold anything, also NaN or Inf
-          t[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
-          t[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
-          if (!ok_a) va[r] = make_uint4(0, 0, 0, 0);
-          if (!ok_b) vb[r] = make_uint4(0, 0, 0, 0);
-        }
+      for (int r = 0; r < 4; ++r) {
+        t[r] = fmaf(sa[r], scale_log2, lane_bias);
+        t[4 + r] = fmaf(sb[r], scale_log2, lane_bias);
       }
-      float lm = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
-      if (__any(lm > m_ref + AT_LAZY_MAX)) {
-        // renew the reference: maximum over the four lane groups of each head column
-        float x = lm;
-        x = fmaxf(x, __shfl_xor(x, 16, 64));
-        x = fmaxf(x, __shfl_xor(x, 32, 64));
-        const float m_new = fmaxf(m_ref, x);
-        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-        l_part *= alpha;
-        m_ref = m_new;
-        // accumulator row r (head r) lives in lanes 0..15; its factor sits in lane r
-        float ar[TIM_G];
+    } else {
 #pragma unroll
-        for (int r = 0; r < TIM_G; ++r) ar[r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(alpha), r));
-#pragma unroll
-        for (int mf = 0; mf < 8; ++mf)
-#pragma unroll
-          for (int r = 0; r < TIM_G; ++r) acc[mf][r] *= ar[r];
+      for (int r = 0; r < 4; ++r) {
+        const bool ok_a = 4 * g + r < left_a && ((vis >> (4 * g + r)) & 1u);
+        const bool ok_b = 4 * g + r < left_b && ((vis >> (16 + 4 * g + r)) & 1u);
+        // the select is on the product: a stale row may hold anything, also NaN or Inf
+        t[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
+        t[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
+        if (!ok_a) va[r] = make_uint4(0, 0, 0, 0);
+        if (!ok_b) vb[r] = make_uint4(0, 0, 0, 0);
       }
-      float p[8];
+    }
+    float lm = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+    if (__any(lm > m_ref + AT_LAZY_MAX)) {
+      // renew the reference: maximum over the four lane groups of each head column
+      float x = lm;
+      x = fmaxf(x, __shfl_xor(x, 16, 64));
+      x = fmaxf(x, __shfl_xor(x, 32, 64));
+      const float m_new = fmaxf(m_ref, x);
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+      l_part *= alpha;
+      m_ref = m_new;
+      // accumulator row r (head r) lives in lanes 0..15; its factor sits in lane r
+      float ar[TIM_G];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(t[e] - m_ref);
-        l_part += p[e];
-      }
-      uint4 pw;
-      pw.x = at_pack_bf16(p[0], p[1]);
-      pw.y = at_pack_bf16(p[2], p[3]);
-      pw.z = at_pack_bf16(p[4], p[5]);
-      pw.w = at_pack_bf16(p[6], p[7]);
-      const at_bf16x8 pa = at_as_bf16x8(pw);
+      for (int r = 0; r < TIM_G; ++r) ar[r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(alpha), r));
+#pragma unroll
+      for (int mf = 0; mf < 8; ++mf)
+#pragma unroll
+        for (int r = 0; r < TIM_G; ++r) acc[mf][r] *= ar[r];
+    }
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = __builtin_amdgcn_exp2f(t[e] - m_ref);
+      l_part += p[e];
+    }
+    uint4 pw;
+    pw.x = at_pack_bf16(p[0], p[1]);
+    pw.y = at_pack_bf16(p[2], p[3]);
+    pw.z = at_pack_bf16(p[4], p[5]);
+    pw.w = at_pack_bf16(p[6], p[7]);
+    const at_bf16x8 pa = at_as_bf16x8(pw);
 
-      // 8x8 transpose of 16-bit elements: rows = token slots (A0..A3, B0..B3), columns = dims
-      const uint32_t *ra[8] = {&va[0].x, &va[1].x, &va[2].x, &va[3].x, &vb[0].x, &vb[1].x, &vb[2].x, &vb[3].x};
+    // 8x8 transpose of 16-bit elements: rows = token slots (A0..A3, B0..B3), columns = dims
+    const uint32_t *ra[8] = {&va[0].x, &va[1].x, &va[2].x, &va[3].x, &vb[0].x, &vb[1].x, &vb[2].x, &vb[3].x};
 #pragma unroll
-      for (int mf = 0; mf < 8; ++mf) {
-        uint4 col;
-        uint32_t *cw = &col.x;
+    for (int mf = 0; mf < 8; ++mf) {
+      uint4 col;
+      uint32_t *cw = &col.x;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t x0 = ra[2 * u][mf >> 1], x1 = ra[2 * u + 1][mf >> 1];
-          cw[u] = (mf & 1) ? __builtin_amdgcn_perm(x1, x0, 0x07060302u) : __builtin_amdgcn_perm(x1, x0, 0x05040100u);
-        }
-        acc[mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, at_as_bf16x8(col), acc[mf], 0, 0, 0);
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t x0 = ra[2 * u][mf >> 1], x1 = ra[2 * u + 1][mf >> 1];
+        cw[u] = (mf & 1) ? __builtin_amdgcn_perm(x1, x0, 0x07060302u) : __builtin_amdgcn_perm(x1, x0, 0x05040100u);
       }
+      acc[mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, at_as_bf16x8(col), acc[mf], 0, 0, 0);
     }
   }
 
@@ -625,8 +630,8 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   }
   __syncthreads();
   at_check_live(st, ws, b, n);
-  at_finish<AT_WAVES, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
-                                used);
+  at_finish<WAVES, 64 * WAVES, OUT_BF16>(cfg, ws, out, &red_m[0][0], &red_l[0][0], &red_o[0][0][0], b, kvh, slot, slots,
+                                         used);
 }
 
 // Log-sum-exp merge of the slot partials: one block of 128 threads per (sequence, query
@@ -715,22 +720,34 @@ extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
          (AT_SCHED_HDR + (4 * (int64_t)AT_MAX_SLOTS + 1) * cfg->max_batch) * (int64_t)sizeof(int32_t);
 }
 
-// Launch shape for a bound on the longest sequence: chunks per block and slots.
-static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int *slots_out) {
+// Launch shape for a bound on the longest sequence: chunks per block, slots, and waves per block.
+// A launch of many blocks uses blocks of 4 waves, three to a CU.  A launch of few blocks - short working
+// memories in a small batch, the regime right after the flushes - would leave most of a CU's wave slots empty
+// and, to fill them, used to cut every sequence into several blocks whose partial results then cost a second
+// kernel; instead its blocks are made wider (12 waves when there is at most one block per CU, 6 when at most
+// two), so the CU still holds twelve waves and a short sequence stays in one block with no partial at all.
+static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int *slots_out, int *waves_out) {
   const tim_config &cfg = ctx->cfg;
   const int full = cfg.max_pages_per_seq * cfg.page_size;
   const int bound = (max_seq_len == 0 || max_seq_len > full) ? full : max_seq_len;
   const int max_pages = (bound + TIM_PS - 1) / TIM_PS;
   const int nchunks = (max_pages + AT_CHUNK_PAGES - 1) / AT_CHUNK_PAGES;
-  const int rows = cfg.max_batch * cfg.kv_heads;
-  // chunks per block: as many as still leave enough blocks to fill the chip several times
+  const int64_t rows = (int64_t)cfg.max_batch * cfg.kv_heads;
   int cpb = ctx->attn_cpb;
-  while (cpb > 1 && (int64_t)rows * ((nchunks + cpb - 1) / cpb) < ctx->attn_fill * (int64_t)ctx->n_cu) --cpb;
+  int waves = ctx->block_waves;
+  if (waves == 0) {
+    const int64_t blocks = rows * ((nchunks + cpb - 1) / cpb);
+    waves = blocks <= ctx->n_cu ? 12 : blocks <= 2 * (int64_t)ctx->n_cu ? 6 : 4;
+    if (ctx->attn_impl != TIM_ATTN_MFMA) waves = 4;  // the vector-ALU kernel has one block shape
+  }
+  // chunks per block: as many as still leave `fill` blocks' worth of waves (4 each) per CU
+  while (cpb > 1 && rows * ((nchunks + cpb - 1) / cpb) * waves < ctx->attn_fill * (int64_t)AT_WAVES * ctx->n_cu) --cpb;
   int slots = (nchunks + cpb - 1) / cpb;
   if (slots > AT_MAX_SLOTS) slots = AT_MAX_SLOTS;
   if (slots < 1) slots = 1;
   *cpb_out = cpb;
   *slots_out = slots;
+  *waves_out = waves;
 }
 
 // The work list of at_take_work.  One block; thread b (and b + blockDim.x, ...) handles sequence b; quadratic in
@@ -784,7 +801,7 @@ tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sch
 
 extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream stream) {
   if (!ctx || !ctx->bound || max_seq_len < 0 || !ctx->st.attn_ws) return TIM_ERR_INVALID_ARG;
-  at_shape(ctx, max_seq_len, &ctx->sched_cpb, &ctx->sched_slots);
+  at_shape(ctx, max_seq_len, &ctx->sched_cpb, &ctx->sched_slots, &ctx->sched_waves);
   // Nothing to gain when every block of the bound's grid is resident at once (idle blocks then cost nothing,
   // and on configuration 4, 117 MB per launch, the list's order paired blocks on CUs worse than the grid's:
   // 29.5 vs 27.0 us per launch), or when there is one sequence: the calls then run unscheduled.
@@ -813,20 +830,32 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
 
 template <int IMPL, bool OUT_BF16>  // 0 = vector ALU, 1 = matrix cores, 2 = matrix cores with visibility mask
 static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, int layer, const void *q, void *out,
-                      float scale_log2, int cpb, int slots, const void *k_new, const void *v_new) {
+                      float scale_log2, int cpb, int slots, int waves, const void *k_new, const void *v_new) {
   const bool ps1 = ctx->cfg.page_size == 1;
-  auto kernel = IMPL == 2   ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, true, true> : tim_attn_partial_mfma_kernel<OUT_BF16, true, false>)
-                : IMPL == 1 ? (ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, false, true> : tim_attn_partial_mfma_kernel<OUT_BF16, false, false>)
-                            : tim_attn_partial_kernel<OUT_BF16>;
+  typedef void (*kernel_t)(tim_config, tim_state, AttnWs, int, const uint4 *, void *, float, int, int, const uint4 *,
+                           const uint4 *);
+  kernel_t kernel;
+  if (IMPL == 0) {
+    kernel = tim_attn_partial_kernel<OUT_BF16>;
+    waves = AT_WAVES;
+  } else if (waves == 12) {
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 12> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 12>;
+  } else if (waves == 6) {
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 6> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 6>;
+  } else {
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 4> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 4>;
+    waves = 4;
+  }
+  const dim3 block(64 * waves);
   const uint4 *q4 = reinterpret_cast<const uint4 *>(q);
   const uint4 *kn = reinterpret_cast<const uint4 *>(k_new), *vn = reinterpret_cast<const uint4 *>(v_new);
   if (ctx->timing_on && ctx->timing_n < (int)ctx->ev_start.size()) {
     // events attached to the dispatch itself: the kernel's own begin/end, no extra barrier
     const int i = ctx->timing_n++;
-    hipExtLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->ev_start[i], ctx->ev_stop[i], 0, ctx->cfg, ctx->st,
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ctx->ev_start[i], ctx->ev_stop[i], 0, ctx->cfg, ctx->st,
                           ws, layer, q4, out, scale_log2, cpb, slots, kn, vn);
   } else {
-    hipLaunchKernelGGL(kernel, grid, dim3(AT_THREADS), 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb,
+    hipLaunchKernelGGL(kernel, grid, block, 0, s, ctx->cfg, ctx->st, ws, layer, q4, out, scale_log2, cpb,
                        slots, kn, vn);
   }
 }
@@ -909,7 +938,7 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
       (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
     return TIM_ERR_INVALID_ARG;
   const tim_config &cfg = ctx->cfg;
-  int cpb, slots;
+  int cpb, slots, waves;
   AttnWs ws;
   ws.ml = ws.o = nullptr;
   ws.sched = nullptr;
@@ -927,7 +956,7 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
     float *base = nullptr;
     const int rc = at_noalloc_scratch(&base);
     if (rc != TIM_OK) return rc;
-    at_shape(ctx, max_seq_len, &cpb, &slots);
+    at_shape(ctx, max_seq_len, &cpb, &slots, &waves);
     const int fit = (int)((int64_t)TIM_NOALLOC_SCRATCH_BYTES / per_slot);
     if (slots > fit) slots = fit;
     ws.ml = base;
@@ -936,24 +965,25 @@ static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, floa
   } else if (ctx->sched_valid) {  // the schedule's shape, not this call's bound: the merge must see the same slots
     cpb = ctx->sched_cpb;
     slots = ctx->sched_slots;
+    waves = ctx->sched_waves;
     ws.sched = reinterpret_cast<const int32_t *>(ctx->st.attn_ws + at_partials_words(cfg));
     grid = dim3(cfg.max_batch * cfg.kv_heads * slots);  // an upper bound on the list's length
   } else {
-    at_shape(ctx, max_seq_len, &cpb, &slots);
+    at_shape(ctx, max_seq_len, &cpb, &slots, &waves);
     grid = dim3(cfg.max_batch * cfg.kv_heads, slots);
   }
   const float scale_log2 = sm_scale * 1.4426950408889634f;
   hipStream_t s = tim_hs(stream);
   const bool bf = out_dtype == TIM_OUT_BF16;
   if (masked) {
-    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
-    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    if (bf) at_launch<2, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
+    else at_launch<2, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
   } else if (ctx->attn_impl == 1) {
-    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
-    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    if (bf) at_launch<1, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
+    else at_launch<1, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
   } else {
-    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
-    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, k_new, v_new);
+    if (bf) at_launch<0, true>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
+    else at_launch<0, false>(grid, s, ctx, ws, layer, q, out, scale_log2, cpb, slots, waves, k_new, v_new);
   }
   TIM_LAUNCH_CHECK();
   if (slots > 1) {  // with one slot every block has already written its final output

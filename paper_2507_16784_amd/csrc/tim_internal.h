@@ -22,9 +22,10 @@ struct tim_ctx {
   int attn_impl;  // tim_attn_impl: matrix-core attention (default) or vector-ALU attention
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
+  int block_waves = 0;  // tim_tuning.block_waves: 0 = chosen per launch, else 4, 6 or 12
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
-  int sched_cpb = 0, sched_slots = 0;
+  int sched_cpb = 0, sched_slots = 0, sched_waves = 4;
   int grade_big = 32, grade_small = 8;  // graded block sizes along the schedule, in 1/16 rounds of work to go
   int round_items = 0;         // tim_tuning.round_items: > 0 = a round of the schedule is this many blocks, and even
                                // launches that fit the chip at once are scheduled (small shapes in tests)

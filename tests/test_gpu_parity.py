@@ -384,6 +384,74 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
     assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("page_size", [16, 1])
+@pytest.mark.parametrize("waves", [4, 6, 12])
+def test_every_block_width_of_the_attention_kernel(gb, waves, page_size):
+    """The library picks 4, 6 or 12 waves per attention block from the size of the launch; here each width is
+    forced (tim_tuning.block_waves) on one batch of very unequal lengths, so that every width meets split and
+    unsplit sequences, ragged last pages and pairs, empty sequences, the work list, the fused append, bf16
+    partials and the visibility mask, whatever the library would have picked for shapes this small."""
+    from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
+    from oracle import attention, bf16
+    lens = [300, 9000, 17, 0, 2500, 1, 4096, 16, 700, 33, 12289]
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * len(lens), lens, 2, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=16 * (16 // page_size),
+                              page_size=page_size, max_nodes=4)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 88, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0, tuning=dict(block_waves=waves, round_items=4))
+    gb.preload_gpu(gpu, wl, 88, 1.0)
+    assert gpu.ctx.tim_ctx_get_tuning().block_waves == waves
+
+    def definition(q_bits, masked=False):
+        out = np.zeros((len(lens), 8, 128), dtype=np.float32)
+        for b in range(len(lens)):
+            n = int(ora.seq_len[b])
+            keep = ora.visible[b, :n] if masked else np.ones(n, dtype=bool)
+            if keep.any():
+                kb, vb = ora.gather_kv(0, b)
+                out[b] = attention.attend(bf16.to_f64(q_bits[b]), bf16.to_f64(kb[keep]), bf16.to_f64(vb[keep]), 128 ** -0.5)
+        return out
+
+    q, _, _ = harness.step_inputs(88, 0, cfg, 1.0)
+    want = definition(q[0])
+    for scheduled in (False, True):
+        gpu.scheduled = scheduled
+        gpu._sched_fresh = False
+        for hint in (0, max(lens)):
+            gpu.max_len_hint = hint
+            gpu._sched_fresh = False
+            for dt in (torch.float32, torch.bfloat16):
+                got = gpu.decode_attn(0, q[0], 128 ** -0.5, out_dtype=dt)
+                check_attention(got, want)
+                assert np.all(got[3] == 0)
+    # two decode steps with the fused append, scheduled
+    gpu.fused_append = True
+    for step in range(2):
+        want_s = harness.run_step(ora, wl, step, 88, 1.0, 128 ** -0.5)
+        got_s = harness.run_step(gpu, wl, step, 88, 1.0, 128 ** -0.5)
+        check_attention(got_s[0], want_s[0])
+    check_state(ora, gpu)
+    check_kv(ora, gpu)
+    # the visibility mask: hide a span of the longest sequences and all of a short one
+    ops = [(1, MARK_OPEN, 0, 0), (1, MARK_SUB_BEGIN, 0, 100), (1, MARK_SUB_END, 0, 8000),
+           (10, MARK_OPEN, 0, 0), (10, MARK_SUB_BEGIN, 0, 31), (10, MARK_SUB_END, 0, 12001),
+           (2, MARK_OPEN, 0, 0), (2, MARK_SUB_BEGIN, 0, 0), (2, MARK_SUB_END, 0, 19)]
+    ora.mark(ops); gpu.mark(ops)
+    ora.prune_mask(range(len(lens))); gpu.prune_mask(range(len(lens)))
+    assert np.array_equal(gpu.visible()[:, : ora.visible.shape[1]], ora.visible)
+    want_m = definition(q[0], masked=True)
+    for scheduled in (False, True):
+        gpu.scheduled = scheduled
+        gpu._sched_fresh = False
+        for dt in (torch.float32, torch.bfloat16):
+            got = gpu.decode_attn_masked(0, q[0], 128 ** -0.5, out_dtype=dt)
+            check_attention(got, want_m)
+            assert np.all(got[2] == 0)
+    assert gpu.status() == 0
+
+
 def test_schedule_is_left_out_where_it_cannot_pay(gb):
     """With the library's own tuning, a launch whose whole grid fits the chip at once stays unscheduled:
     tim_attn_schedule returns success and does nothing, and a later change of a length is no error."""
