@@ -498,6 +498,8 @@ def main():
                          "the kernel-level roofline pass still runs eagerly")
     ap.add_argument("--page-size", type=int, default=16, choices=[16, 1],
                     help="16 (default) or 1, the paper's own page size: flushes then move no rows")
+    ap.add_argument("--tune", default="",
+                    help="A/B measurements: fields of tim_tuning to override, e.g. block_waves=6,chunks_per_block=8")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
@@ -547,6 +549,8 @@ def main():
     shape.q_scale = 128 ** -0.5
     ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=headroom, layers_alloc=args.layers_alloc,
                                  seed=args.seed, page_size=args.page_size)
+    if args.tune:
+        ctx.tim_ctx_set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     plan = tim.Plan(ctx.cfg, args.batch)
     B = args.batch
     g = torch.Generator(device="cuda")
@@ -665,7 +669,7 @@ def main():
         "hbm_frac_of_peak": round(total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 4),
         "config": {"workload": shape.name, "batch": B, "layers": shape.layers, "layers_allocated": L_alloc,
                    "q_heads": shape.q_heads, "kv_heads": shape.kv_heads, "head_dim": 128, "page_size": args.page_size,
-                   "threshold": shape.threshold, "hip_graph": bool(args.graph), "positions_per_seq": [int(min(wl.preload)), int(max(wl.preload))],
+                   "threshold": shape.threshold, "hip_graph": bool(args.graph), "tuning_override": args.tune or None, "positions_per_seq": [int(min(wl.preload)), int(max(wl.preload))],
                    "big_flushes": len(big_ratios),
                    "mean_prune_ratio_big_flush": round(float(np.mean(big_ratios)), 4) if big_ratios else None,
                    "moved_tokens": moved, "flush_calls": len(record["hdr"]),

@@ -201,7 +201,7 @@ typedef struct {
                                 this many blocks, and tim_attn_schedule schedules even launches that fit the
                                 chip at once or hold one sequence (small shapes then reach all block sizes) */
   int32_t block_waves;       /* default 0: waves per attention block chosen per launch (12 when the launch holds at
-                                most one block per CU, 6 when at most two, else 4); 4, 6 or 12 forces one */
+                                most one block per CU, 6 when at most two, else 4); 4, 6, 8 or 12 forces one */
 } tim_tuning;
 int tim_ctx_get_tuning(const tim_ctx *ctx, tim_tuning *out);
 int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *tuning);

@@ -440,50 +440,68 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   int next_ids = 0;
   if (PS1) next_ids = load_row_ids(min(unit, n_pairs - 1));
 
-  int k = 0;
-  for (int pr = unit; pr < n_pairs; pr += stride, ++k) {
-    const int pg = 2 * pr;
-    const bool has_b = pg + 1 < n_pages;
+  // One pair of pages in registers: the K and V tiles of pages A and B, where they start in the pools (16-byte
+  // units; page size 1: unused) and, in the in-forward variant, the visibility of the pair's 32 tokens.
+  // (handed over by value: through references the compiler kept the tiles in scratch memory)
+  struct Tiles {
+    uint4 ka[4], kb[4], va[4], vb[4];
+    int64_t row_a, row_b;
+    uint32_t vis;
+  };
+
+  // Moves the page-id pipeline on to pair `pr`, the wave's k-th pair; called once per pair, in order, also for a
+  // pair that is then skipped.
+  int my_ids = 0;
+  auto advance_ids = [&](int pr, int k) __attribute__((always_inline)) {
     if (!PS1 && (k & 31) == 0) {  // the ids of this and the next 31 pairs arrive; those of the 32 after them are requested
       my_pid = next_pid;
       if ((int64_t)pr + 32 * (int64_t)stride < n_pairs) next_pid = load_pids(k + 32);
     }
-    int my_ids = next_ids;
+    my_ids = next_ids;
     if (PS1) next_ids = load_row_ids(min(pr + stride, n_pairs - 1));
-    // in-forward variant: visibility of the pair's 32 tokens; a pair without a visible token is not read at all
-    uint32_t vis = 0xffffffffu;
-    if (MASKED) {
-      vis = __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * tim_mask_words(cfg) + pr]);
-      if (vis == 0) continue;
-    }
-    uint4 ka[4], kb[4], va[4], vb[4];
-    int64_t row_a = 0, row_b = 0;  // 16-byte units: start of page A's / page B's tile (page size 1: unused)
+  };
+  // In-forward variant: visibility of the pair's 32 tokens; a pair without a visible token is not read at all.
+  auto visibility = [&](int pr) __attribute__((always_inline)) -> uint32_t {
+    if (!MASKED) return 0xffffffffu;
+    return __builtin_amdgcn_readfirstlane(st.keep_mask[(int64_t)b * tim_mask_words(cfg) + pr]);
+  };
+
+  // Requests the tiles of pair `pr`, the wave's k-th pair, after advance_ids(pr, k).
+  auto issue = [&](int pr, int k, uint32_t vis_) __attribute__((always_inline)) -> Tiles {
+    Tiles t;
+    uint4 (&t_ka)[4] = t.ka, (&t_kb)[4] = t.kb, (&t_va)[4] = t.va, (&t_vb)[4] = t.vb;
+    int64_t &t_row_a = t.row_a, &t_row_b = t.row_b;
+    const int pg = 2 * pr;
+    const bool has_b = pg + 1 < n_pages;
+    t.vis = vis_;
+    t_row_a = t_row_b = 0;
     if (PS1) {
       // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  K rows are read
       // in 64-byte pieces by four instructions and need the L1 (ordinary loads; non-temporal ones measured 6 %
       // slower); a V row is read whole by one instruction: non-temporal, +4 %.
-      if (my_ids < 0 || my_ids >= cfg.num_pages) {  // never dereference a bad page id
+      int ids_ok = my_ids;
+      if (ids_ok < 0 || ids_ok >= cfg.num_pages) {  // never dereference a bad page id
         tim_set_status(st.status, TIM_ERR_INVALID_ARG);
-        my_ids = 0;
+        ids_ok = 0;
       }
       const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
       int ids[10];
-      ids[0] = __shfl(my_ids, j, 64);
-      ids[1] = __shfl(my_ids, off_b + j, 64);
+      ids[0] = __shfl(ids_ok, j, 64);
+      ids[1] = __shfl(ids_ok, off_b + j, 64);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        ids[2 + i] = __shfl(my_ids, 4 * g + i, 64);
-        ids[6 + i] = __shfl(my_ids, off_b + 4 * g + i, 64);
+        ids[2 + i] = __shfl(ids_ok, 4 * g + i, 64);
+        ids[6 + i] = __shfl(ids_ok, off_b + 4 * g + i, 64);
       }
       const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ka[s] = kpool[ra + 4 * s + g];
+      for (int s = 0; s < 4; ++s) t_ka[s] = kpool[ra + 4 * s + g];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) kb[s] = kpool[rb + 4 * s + g];
+      for (int s = 0; s < 4; ++s) t_kb[s] = kpool[rb + 4 * s + g];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
+      for (int i = 0; i < 4; ++i) t_va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
+      for (int i = 0; i < 4; ++i) t_vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
     } else {
       int phys_a = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31));
       int phys_b = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31) + (has_b ? 1 : 0));
@@ -491,18 +509,28 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         tim_set_status(st.status, TIM_ERR_INVALID_ARG);  // never dereference a bad page id
         phys_a = phys_b = 0;
       }
-      row_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
-      row_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+      t_row_a = ((layer_base + phys_a) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
+      t_row_b = ((layer_base + phys_b) * cfg.kv_heads + kvh) * (TIM_TILE_BYTES / 16);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ka[s] = tim_load_stream(kpool + row_a + j * 16 + 4 * s + g);
+      for (int s = 0; s < 4; ++s) t_ka[s] = tim_load_stream(kpool + t_row_a + j * 16 + 4 * s + g);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) kb[s] = tim_load_stream(kpool + row_b + j * 16 + 4 * s + g);
+      for (int s = 0; s < 4; ++s) t_kb[s] = tim_load_stream(kpool + t_row_b + j * 16 + 4 * s + g);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) va[i] = tim_load_stream(vpool + row_a + (4 * g + i) * 16 + j);
+      for (int i = 0; i < 4; ++i) t_va[i] = tim_load_stream(vpool + t_row_a + (4 * g + i) * 16 + j);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) vb[i] = tim_load_stream(vpool + row_b + (4 * g + i) * 16 + j);
+      for (int i = 0; i < 4; ++i) t_vb[i] = tim_load_stream(vpool + t_row_b + (4 * g + i) * 16 + j);
     }
+    return t;
+  };
 
+  // Scores, weights and output products of pair `pr`, whose tiles `issue` requested.
+  auto process = [&](int pr, Tiles t) __attribute__((always_inline)) {
+    uint4 (&t_ka)[4] = t.ka, (&t_kb)[4] = t.kb, (&t_va)[4] = t.va, (&t_vb)[4] = t.vb;
+    const int64_t t_row_a = t.row_a, t_row_b = t.row_b;
+    const uint32_t t_vis = t.vis;
+    const int pg = 2 * pr;
+    const bool has_b = pg + 1 < n_pages;
+    const uint32_t vis = t_vis;
     // fused append: the wave that owns the sequence's last page takes the pending token's
     // row from the caller's buffers instead of the pool, and stores it into the pool
     if (k_new != nullptr) {
@@ -515,24 +543,28 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
           if (sid < 0 || sid >= cfg.num_pages) sid = 0;  // reported by the loads above
           krow = ((layer_base + sid) * cfg.kv_heads + kvh) * 16;
         } else {
-          krow = (in_b ? row_b : row_a) + row * 16;
+          krow = (in_b ? t_row_b : t_row_a) + row * 16;
         }
         const int64_t src = ((int64_t)b * cfg.kv_heads + kvh) * 16;
         if (j == row) {
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
             const uint4 x = k_new[src + 4 * s + g];
-            if (in_b) kb[s] = x; else ka[s] = x;
+            if (in_b) t_kb[s] = x;
+            if (!in_b) t_ka[s] = x;
             const_cast<uint4 *>(kpool)[krow + 4 * s + g] = x;
           }
         }
         if ((row >> 2) == g) {
           const uint4 x = v_new[src + j];
+          // (written as selects on every slot: an index computed at run time would move the tiles to scratch memory)
+          auto pick = [](bool c, const uint4 &a2, const uint4 &b2) { return make_uint4(c ? a2.x : b2.x, c ? a2.y : b2.y, c ? a2.z : b2.z, c ? a2.w : b2.w); };
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (i == (row & 3)) {
-              if (in_b) vb[i] = x; else va[i] = x;
-            }
+          for (int i = 0; i < 4; ++i) {
+            const bool hit = i == (row & 3);
+            t_va[i] = pick(hit && !in_b, x, t_va[i]);
+            t_vb[i] = pick(hit && in_b, x, t_vb[i]);
+          }
           const_cast<uint4 *>(vpool)[krow + j] = x;
         }
       }
@@ -545,16 +577,16 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
 
     at_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < 4; ++s) sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(ka[s]), at_as_bf16x8(qb[s]), sa, 0, 0, 0);
+    for (int s = 0; s < 4; ++s) sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(t_ka[s]), at_as_bf16x8(qb[s]), sa, 0, 0, 0);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(kb[s]), at_as_bf16x8(qb[s]), sb, 0, 0, 0);
+    for (int s = 0; s < 4; ++s) sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(at_as_bf16x8(t_kb[s]), at_as_bf16x8(qb[s]), sb, 0, 0, 0);
 
-    float t[8];
+    float tt[8];
     if (full) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        t[r] = fmaf(sa[r], scale_log2, lane_bias);
-        t[4 + r] = fmaf(sb[r], scale_log2, lane_bias);
+        tt[r] = fmaf(sa[r], scale_log2, lane_bias);
+        tt[4 + r] = fmaf(sb[r], scale_log2, lane_bias);
       }
     } else {
 #pragma unroll
@@ -562,13 +594,13 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
         const bool ok_a = 4 * g + r < left_a && ((vis >> (4 * g + r)) & 1u);
         const bool ok_b = 4 * g + r < left_b && ((vis >> (16 + 4 * g + r)) & 1u);
         // the select is on the product: a stale row may hold anything, also NaN or Inf
-        t[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
-        t[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
-        if (!ok_a) va[r] = make_uint4(0, 0, 0, 0);
-        if (!ok_b) vb[r] = make_uint4(0, 0, 0, 0);
+        tt[r] = ok_a ? fmaf(sa[r], scale_log2, lane_bias) : -INFINITY;
+        tt[4 + r] = ok_b ? fmaf(sb[r], scale_log2, lane_bias) : -INFINITY;
+        if (!ok_a) t_va[r] = make_uint4(0, 0, 0, 0);
+        if (!ok_b) t_vb[r] = make_uint4(0, 0, 0, 0);
       }
     }
-    float lm = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+    float lm = fmaxf(fmaxf(fmaxf(tt[0], tt[1]), fmaxf(tt[2], tt[3])), fmaxf(fmaxf(tt[4], tt[5]), fmaxf(tt[6], tt[7])));
     if (__any(lm > m_ref + AT_LAZY_MAX)) {
       // renew the reference: maximum over the four lane groups of each head column
       float x = lm;
@@ -590,7 +622,7 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     float p[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = __builtin_amdgcn_exp2f(t[e] - m_ref);
+      p[e] = __builtin_amdgcn_exp2f(tt[e] - m_ref);
       l_part += p[e];
     }
     uint4 pw;
@@ -601,18 +633,32 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     const at_bf16x8 pa = at_as_bf16x8(pw);
 
     // 8x8 transpose of 16-bit elements: rows = token slots (A0..A3, B0..B3), columns = dims
-    const uint32_t *ra[8] = {&va[0].x, &va[1].x, &va[2].x, &va[3].x, &vb[0].x, &vb[1].x, &vb[2].x, &vb[3].x};
+    auto word = [&](int r, int c) -> uint32_t {  // 32-bit word c of token slot r (constants once unrolled)
+      const uint4 &x = r < 4 ? t_va[r & 3] : t_vb[r & 3];
+      return c == 0 ? x.x : c == 1 ? x.y : c == 2 ? x.z : x.w;
+    };
 #pragma unroll
     for (int mf = 0; mf < 8; ++mf) {
-      uint4 col;
-      uint32_t *cw = &col.x;
+      uint32_t cw[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const uint32_t x0 = ra[2 * u][mf >> 1], x1 = ra[2 * u + 1][mf >> 1];
+        const uint32_t x0 = word(2 * u, mf >> 1), x1 = word(2 * u + 1, mf >> 1);
         cw[u] = (mf & 1) ? __builtin_amdgcn_perm(x1, x0, 0x07060302u) : __builtin_amdgcn_perm(x1, x0, 0x05040100u);
       }
-      acc[mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, at_as_bf16x8(col), acc[mf], 0, 0, 0);
+      acc[mf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, at_as_bf16x8(make_uint4(cw[0], cw[1], cw[2], cw[3])), acc[mf], 0, 0, 0);
     }
+  };
+
+  // (Requesting a wave's next pair before working on the current one, with two register sets that swap roles,
+  // was measured and rejected: at 256 registers the compiler spills about 50 of them inside the loop and a CU
+  // holds 8 waves instead of 12: 35.4 against 50.5 decode steps/s on long working memories, 37.8 against 26.1 us
+  // per launch on short ones.)
+  int k = 0;
+  for (int pr = unit; pr < n_pairs; pr += stride, ++k) {
+    advance_ids(pr, k);
+    const uint32_t vis = visibility(pr);
+    if (MASKED && vis == 0) continue;
+    process(pr, issue(pr, k, vis));
   }
 
   // row sums: add the four lane groups of each head column
@@ -835,15 +881,18 @@ static void at_launch(dim3 grid, hipStream_t s, tim_ctx *ctx, const AttnWs &ws, 
   typedef void (*kernel_t)(tim_config, tim_state, AttnWs, int, const uint4 *, void *, float, int, int, const uint4 *,
                            const uint4 *);
   kernel_t kernel;
+  constexpr bool M = IMPL == 2;
   if (IMPL == 0) {
     kernel = tim_attn_partial_kernel<OUT_BF16>;
     waves = AT_WAVES;
   } else if (waves == 12) {
-    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 12> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 12>;
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, M, true, 12> : tim_attn_partial_mfma_kernel<OUT_BF16, M, false, 12>;
+  } else if (waves == 8) {
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, M, true, 8> : tim_attn_partial_mfma_kernel<OUT_BF16, M, false, 8>;
   } else if (waves == 6) {
-    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 6> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 6>;
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, M, true, 6> : tim_attn_partial_mfma_kernel<OUT_BF16, M, false, 6>;
   } else {
-    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, true, 4> : tim_attn_partial_mfma_kernel<OUT_BF16, IMPL == 2, false, 4>;
+    kernel = ps1 ? tim_attn_partial_mfma_kernel<OUT_BF16, M, true, 4> : tim_attn_partial_mfma_kernel<OUT_BF16, M, false, 4>;
     waves = 4;
   }
   const dim3 block(64 * waves);

@@ -48,7 +48,7 @@ extern "C" int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *t) {
   if (!ctx || !t) return TIM_ERR_INVALID_ARG;
   if ((t->attn_impl != TIM_ATTN_VALU && t->attn_impl != TIM_ATTN_MFMA) || t->chunks_per_block < 1 ||
       t->chunks_per_block > 64 || t->fill < 1 || t->fill > 64 || t->grade_small < 0 || t->grade_big < t->grade_small ||
-      t->round_items < 0 || (t->block_waves != 0 && t->block_waves != 4 && t->block_waves != 6 && t->block_waves != 12))
+      t->round_items < 0 || (t->block_waves != 0 && t->block_waves != 4 && t->block_waves != 6 && t->block_waves != 8 && t->block_waves != 12))
     return TIM_ERR_INVALID_ARG;
   ctx->attn_impl = t->attn_impl;
   ctx->attn_cpb = t->chunks_per_block;

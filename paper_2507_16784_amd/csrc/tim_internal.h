@@ -22,7 +22,7 @@ struct tim_ctx {
   int attn_impl;  // tim_attn_impl: matrix-core attention (default) or vector-ALU attention
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
-  int block_waves = 0;  // tim_tuning.block_waves: 0 = chosen per launch, else 4, 6 or 12
+  int block_waves = 0;  // tim_tuning.block_waves: 0 = chosen per launch, else 4, 6, 8 or 12
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
   int sched_cpb = 0, sched_slots = 0, sched_waves = 4;

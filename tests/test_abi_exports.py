@@ -53,7 +53,7 @@ def test_host_side_argument_checks_need_no_gpu():
     t2 = tim.tim_tuning()
     assert lib.tim_ctx_get_tuning(h, ctypes.byref(t2)) == tim.OK and (t2.chunks_per_block, t2.round_items) == (3, 4)
     for field, bad_value in (("attn_impl", 2), ("chunks_per_block", 0), ("chunks_per_block", 65), ("fill", 0),
-                             ("grade_small", 33), ("grade_small", -1), ("round_items", -1), ("block_waves", 8)):
+                             ("grade_small", 33), ("grade_small", -1), ("round_items", -1), ("block_waves", 5)):
         t3 = tim.tim_tuning()
         lib.tim_ctx_get_tuning(h, ctypes.byref(t3))
         setattr(t3, field, bad_value)

@@ -385,12 +385,12 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
 
 
 @pytest.mark.parametrize("page_size", [16, 1])
-@pytest.mark.parametrize("waves", [4, 6, 12])
+@pytest.mark.parametrize("waves", [4, 6, 8, 12])
 def test_every_block_width_of_the_attention_kernel(gb, waves, page_size):
-    """The library picks 4, 6 or 12 waves per attention block from the size of the launch; here each width is
-    forced (tim_tuning.block_waves) on one batch of very unequal lengths, so that every width meets split and
-    unsplit sequences, ragged last pages and pairs, empty sequences, the work list, the fused append, bf16
-    partials and the visibility mask, whatever the library would have picked for shapes this small."""
+    """The library picks the waves per attention block from the size of the launch; here each width is forced
+    (tim_tuning.block_waves) on one batch of very unequal lengths, so that every width meets split and unsplit
+    sequences, ragged last pages and pairs, empty sequences, the work list, the fused append, bf16 partials and
+    the visibility mask, whatever the library would have picked for shapes this small."""
     from paper_2507_16784_amd.workload.tree import MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Trace
     from oracle import attention, bf16
     lens = [300, 9000, 17, 0, 2500, 1, 4096, 16, 700, 33, 12289]
