@@ -70,6 +70,7 @@ __device__ __forceinline__ void at_store_out(void *out, int64_t idx, float v) {
 }
 
 
+typedef __attribute__((address_space(3))) void *at_lds_ptr;
 typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float at_f32x4 __attribute__((ext_vector_type(4)));
@@ -395,11 +396,15 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   __shared__ float red_m[WAVES][TIM_G];
   __shared__ float red_l[WAVES][TIM_G];
   __shared__ float red_o[WAVES][TIM_G][TIM_D];
+  // Page size 1 only: each wave's key rows of one pair of "pages" (32 tokens), copied there straight from global
+  // memory as whole 256-byte rows and read back in the matrix operand's layout (see issue / process below).
+  __shared__ uint4 kstage[PS1 ? WAVES : 1][PS1 ? 2 * TIM_PS : 1][16];
 
   AtWork wk;
   if (!at_take_work<OUT_BF16>(cfg, st, ws, out, slots, cpb, wk)) return;
   const int b = wk.b, kvh = wk.kvh, slot = wk.slot, n = wk.n, used = wk.used;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, g = lane >> 4, j = lane & 15;
+  const int wu = __builtin_amdgcn_readfirstlane(w);  // the same number where the compiler must see it is wave-uniform
   const int n_pages = (n + TIM_PS - 1) / TIM_PS;
   const int n_pairs = (n_pages + 1) >> 1;
   const int unit = slot * WAVES + w, stride = used * WAVES;  // this wave's pairs: unit, unit + stride, ...
@@ -476,32 +481,35 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     t.vis = vis_;
     t_row_a = t_row_b = 0;
     if (PS1) {
-      // one page per token: the K operand row j and the V rows 4g+i each bring their own id.  K rows are read
-      // in 64-byte pieces by four instructions and need the L1 (ordinary loads; non-temporal ones measured 6 %
-      // slower); a V row is read whole by one instruction: non-temporal, +4 %.
+      // One page per token: every row brings its own id.  The operand layout of the score product wants lane
+      // (g, j) to hold 16 bytes of row j, which read straight from memory touches sixteen rows in 64-byte pieces
+      // per instruction (that needed the L1 and measured 5.98 TB/s against 6.42 with 16-token pages).  Instead both
+      // K and V are fetched as whole rows, 256 bytes per 16 lanes, non-temporally: lane (g, c) takes chunk c of
+      // token 4g + i with load i.  V stays in registers (that is its operand layout).  K goes directly into the
+      // wave's LDS stage (lane order: position 4i + g holds token 4g + i; chunk c sits in slot c ^ position, so
+      // that the operand reads below are free of bank conflicts) and is read back from there in process().
       int ids_ok = my_ids;
       if (ids_ok < 0 || ids_ok >= cfg.num_pages) {  // never dereference a bad page id
         tim_set_status(st.status, TIM_ERR_INVALID_ARG);
         ids_ok = 0;
       }
       const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
-      int ids[10];
-      ids[0] = __shfl(ids_ok, j, 64);
-      ids[1] = __shfl(ids_ok, off_b + j, 64);
+      int64_t rows[8];  // 16-byte units: start of the row of token 4g + i of page A (i < 4) and of page B
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        ids[2 + i] = __shfl(ids_ok, 4 * g + i, 64);
-        ids[6 + i] = __shfl(ids_ok, off_b + 4 * g + i, 64);
+        rows[i] = ((layer_base + __shfl(ids_ok, 4 * g + i, 64)) * cfg.kv_heads + kvh) * 16;
+        rows[4 + i] = ((layer_base + __shfl(ids_ok, off_b + 4 * g + i, 64)) * cfg.kv_heads + kvh) * 16;
       }
-      const int64_t ra = ((layer_base + ids[0]) * cfg.kv_heads + kvh) * 16, rb = ((layer_base + ids[1]) * cfg.kv_heads + kvh) * 16;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) t_ka[s] = kpool[ra + 4 * s + g];
+      for (int i = 0; i < 8; ++i) {  // copy i fills positions 4 (i % 4) .. + 3 of page i / 4 of the stage, 1 KiB in lane order
+        const int pos = 4 * (i & 3) + g;
+        __builtin_amdgcn_global_load_lds(kpool + rows[i] + (j ^ pos), (at_lds_ptr)&kstage[wu][TIM_PS * (i >> 2) + 4 * (i & 3)][0], 16, 0,
+                                         2 /* non-temporal */);
+      }
 #pragma unroll
-      for (int s = 0; s < 4; ++s) t_kb[s] = kpool[rb + 4 * s + g];
+      for (int i = 0; i < 4; ++i) t_va[i] = tim_load_stream(vpool + rows[i] + j);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) t_va[i] = tim_load_stream(vpool + ((layer_base + ids[2 + i]) * cfg.kv_heads + kvh) * 16 + j);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) t_vb[i] = tim_load_stream(vpool + ((layer_base + ids[6 + i]) * cfg.kv_heads + kvh) * 16 + j);
+      for (int i = 0; i < 4; ++i) t_vb[i] = tim_load_stream(vpool + rows[4 + i] + j);
     } else {
       int phys_a = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31));
       int phys_b = __builtin_amdgcn_readlane(my_pid, 2 * (k & 31) + (has_b ? 1 : 0));
@@ -531,6 +539,14 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     const int pg = 2 * pr;
     const bool has_b = pg + 1 < n_pages;
     const uint32_t vis = t_vis;
+    if (PS1) {  // the K operands come out of the wave's stage: token j sits at position 4 (j % 4) + j / 4
+      const int pos = 4 * (j & 3) + (j >> 2);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        t_ka[s] = kstage[wu][pos][(4 * s + g) ^ pos];
+        t_kb[s] = kstage[wu][TIM_PS + pos][(4 * s + g) ^ pos];
+      }
+    }
     // fused append: the wave that owns the sequence's last page takes the pending token's
     // row from the caller's buffers instead of the pool, and stores it into the pool
     if (k_new != nullptr) {
