@@ -441,8 +441,28 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
   // Page size 1: a "page" below is a run of 16 tokens and every row has its own page id.  The ids of a pair's
   // 32 tokens are one load (lane l holds token 32 * pair + l % 32), requested one pair ahead like the page
   // ids above, and handed to the lanes that need them by cross-lane reads.
-  auto load_row_ids = [&](int pr_) { return ptab[(int)min((int64_t)pr_ * (2 * TIM_PS) + (lane & 31), (int64_t)n - 1)]; };
-  int next_ids = 0;
+  struct __attribute__((aligned(4))) RowIds { int a[4], b[4]; };  // ids of tokens 4g .. 4g+3 of page A and of page B
+  auto load_row_ids = [&](int pr_) __attribute__((always_inline)) -> RowIds {
+    RowIds r;
+    const int base = pr_ * (2 * TIM_PS) + 4 * g;
+    if (pr_ * (2 * TIM_PS) + 2 * TIM_PS <= cfg.max_pages_per_seq) {  // the whole pair lies inside the table's row: two 16-byte loads
+      struct __attribute__((aligned(4))) I4 { int v[4]; };
+      const I4 x = *reinterpret_cast<const I4 *>(ptab + base), y = *reinterpret_cast<const I4 *>(ptab + base + TIM_PS);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        r.a[i] = x.v[i];
+        r.b[i] = y.v[i];
+      }
+    } else {  // the row's last, ragged pair: entry by entry, clamped to the row
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        r.a[i] = ptab[min(base + i, cfg.max_pages_per_seq - 1)];
+        r.b[i] = ptab[min(base + TIM_PS + i, cfg.max_pages_per_seq - 1)];
+      }
+    }
+    return r;
+  };
+  RowIds next_ids = {};
   if (PS1) next_ids = load_row_ids(min(unit, n_pairs - 1));
 
   // One pair of pages in registers: the K and V tiles of pages A and B, where they start in the pools (16-byte
@@ -456,7 +476,7 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
 
   // Moves the page-id pipeline on to pair `pr`, the wave's k-th pair; called once per pair, in order, also for a
   // pair that is then skipped.
-  int my_ids = 0;
+  RowIds my_ids = {};
   auto advance_ids = [&](int pr, int k) __attribute__((always_inline)) {
     if (!PS1 && (k & 31) == 0) {  // the ids of this and the next 31 pairs arrive; those of the 32 after them are requested
       my_pid = next_pid;
@@ -488,18 +508,21 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
       // token 4g + i with load i.  V stays in registers (that is its operand layout).  K goes directly into the
       // wave's LDS stage (lane order: position 4i + g holds token 4g + i; chunk c sits in slot c ^ position, so
       // that the operand reads below are free of bank conflicts) and is read back from there in process().
-      int ids_ok = my_ids;
-      if (ids_ok < 0 || ids_ok >= cfg.num_pages) {  // never dereference a bad page id
-        tim_set_status(st.status, TIM_ERR_INVALID_ARG);
-        ids_ok = 0;
-      }
-      const int off_b = has_b ? TIM_PS : 0;  // without a second page its operands repeat the first (masked below)
       int64_t rows[8];  // 16-byte units: start of the row of token 4g + i of page A (i < 4) and of page B
+      bool bad = false;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        rows[i] = ((layer_base + __shfl(ids_ok, 4 * g + i, 64)) * cfg.kv_heads + kvh) * 16;
-        rows[4 + i] = ((layer_base + __shfl(ids_ok, off_b + 4 * g + i, 64)) * cfg.kv_heads + kvh) * 16;
+      for (int i = 0; i < 8; ++i) {
+        // a token past the sequence's end has no page (its table entry may hold anything): row 0 stands in, masked below
+        const int tok = pg * TIM_PS + (i >> 2) * TIM_PS + 4 * g + (i & 3);
+        int id = i < 4 ? my_ids.a[i] : my_ids.b[i - 4];
+        if (tok >= n) id = 0;
+        if (id < 0 || id >= cfg.num_pages) {  // never dereference a bad page id
+          bad = true;
+          id = 0;
+        }
+        rows[i] = ((layer_base + id) * cfg.kv_heads + kvh) * 16;
       }
+      if (bad) tim_set_status(st.status, TIM_ERR_INVALID_ARG);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {  // copy i fills positions 4 (i % 4) .. + 3 of page i / 4 of the stage, 1 KiB in lane order
         const int pos = 4 * (i & 3) + g;
