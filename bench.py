@@ -385,13 +385,15 @@ def horizon_mode(torch, tim, np, configs, args):
     print(json.dumps(res), flush=True)
 
 
-def mix_mode(torch, tim, np):
+def mix_mode(torch, tim, np, tune=""):
     """One decode-attention launch (configuration-3 geometry, one layer) on a batch of very unequal
     lengths: k sequences that have not been flushed yet among 64 - k that have.  Kernel time from the
     dispatch's own events, without and with the per-step work list."""
     B, HQ, HKV, LONG, SHORT = 64, 32, 8, 32000, 2500
     num_pages = 70000
     ctx = tim.Context(1, HQ, HKV, num_pages, B, 2064, 1)
+    if tune:
+        ctx.tim_ctx_set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in tune.split(","))})
     g = torch.Generator(device="cuda")
     g.manual_seed(1)
     q = torch.randn(B, HQ, 128, generator=g, device="cuda").to(torch.bfloat16)
@@ -422,6 +424,16 @@ def mix_mode(torch, tim, np):
             for _ in range(30):
                 ctx.tim_decode_attn(0, q, out, 0.088, max(lens))
             us = float(np.mean(ctx.tim_timing_end())) * 1e3
+            ctx.tim_timing_begin(1)                                   # the same launches back to back, merge kernel included
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(30):
+                ctx.tim_decode_attn(0, q, out, 0.088, max(lens))
+            e1.record()
+            e1.synchronize()
+            ctx.tim_timing_end()
+            row[name + "_us_per_call_back_to_back"] = round(e0.elapsed_time(e1) / 30 * 1e3, 1)
             row[name + "_us"] = round(us, 1)
             row[name + "_GBps"] = round(gb / us * 1e6, 0)
         assert ctx.tim_status() == 0
@@ -527,7 +539,7 @@ def main():
         torch.cuda.empty_cache()
     t_setup = time.perf_counter()
     if args.mode == "mix":
-        mix_mode(torch, tim, np)
+        mix_mode(torch, tim, np, args.tune)
         return
     if args.workload == "config5":
         horizon_mode(torch, tim, np, configs, args)
