@@ -806,11 +806,13 @@ extern "C" int64_t tim_attn_ws_bytes(const tim_config *cfg) {
 }
 
 // Launch shape for a bound on the longest sequence: chunks per block, slots, and waves per block.
-// A launch of many blocks uses blocks of 4 waves, three to a CU.  A launch of few blocks - short working
-// memories in a small batch, the regime right after the flushes - would leave most of a CU's wave slots empty
-// and, to fill them, used to cut every sequence into several blocks whose partial results then cost a second
-// kernel; instead its blocks are made wider (12 waves when there is at most one block per CU, 6 when at most
-// two), so the CU still holds twelve waves and a short sequence stays in one block with no partial at all.
+// Blocks have 4 waves, three to a CU, and a sequence is cut into as many of them as it takes to fill the chip.
+// One case is treated differently: a launch whose longest sequence fits one block anyway and which has at most
+// one or two (sequence, kv head) rows per CU - short working memories in a small batch, the regime right after
+// the flushes.  Cutting those rows further to fill the CUs' wave slots costs a second kernel for the partial
+// results (measured: 31-34 us against 26 us per launch on 256 rows of about 900 tokens); instead the blocks are
+// made wider, 12 waves for one row per CU and 6 for two, so that a CU still holds twelve waves and every
+// sequence stays in one block: no partial, no merge launch.
 static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int *slots_out, int *waves_out) {
   const tim_config &cfg = ctx->cfg;
   const int full = cfg.max_pages_per_seq * cfg.page_size;
@@ -821,9 +823,11 @@ static void at_shape(const tim_ctx *ctx, int32_t max_seq_len, int *cpb_out, int 
   int cpb = ctx->attn_cpb;
   int waves = ctx->block_waves;
   if (waves == 0) {
-    const int64_t blocks = rows * ((nchunks + cpb - 1) / cpb);
-    waves = blocks <= ctx->n_cu ? 12 : blocks <= 2 * (int64_t)ctx->n_cu ? 6 : 4;
-    if (ctx->attn_impl != TIM_ATTN_MFMA) waves = 4;  // the vector-ALU kernel has one block shape
+    waves = AT_WAVES;
+    if (ctx->attn_impl == TIM_ATTN_MFMA && nchunks <= cpb && rows <= 2 * (int64_t)ctx->n_cu) {
+      const int wide = rows <= ctx->n_cu ? 12 : 6;
+      if (rows * wide >= ctx->attn_fill * (int64_t)AT_WAVES * ctx->n_cu) waves = wide;  // else too few rows: cut them after all
+    }
   }
   // chunks per block: as many as still leave `fill` blocks' worth of waves (4 each) per CU
   while (cpb > 1 && rows * ((nchunks + cpb - 1) / cpb) * waves < ctx->attn_fill * (int64_t)AT_WAVES * ctx->n_cu) --cpb;
