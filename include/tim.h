@@ -202,6 +202,8 @@ typedef struct {
                                 chip at once or hold one sequence (small shapes then reach all block sizes) */
   int32_t block_waves;       /* default 0: waves per attention block chosen per launch (12 when the launch holds at
                                 most one block per CU, 6 when at most two, else 4); 4, 6, 8 or 12 forces one */
+  int32_t short_list_chunks; /* default 0: under a schedule, the one block size of a list too short to be graded is
+                                chosen from the lengths; 1..128 fixes it (clamped to chunks_per_block / 2 .. x 2) */
 } tim_tuning;
 int tim_ctx_get_tuning(const tim_ctx *ctx, tim_tuning *out);
 int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *tuning);

@@ -28,6 +28,7 @@
 #define AT_MAX_SLOTS 128
 #define AT_BLOCKS_PER_CU 3  // of the matrix-core kernel: what its registers allow
 #define AT_GRADE_MIN_ROUNDS 3
+#define AT_MAX_CPB 64  // tim_tuning.chunks_per_block is at most this
 #define AT_NEG_BIG (-1.0e30f)
 
 __device__ __forceinline__ float at_bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -854,8 +855,51 @@ __device__ __forceinline__ int at_chunks_of(int n) {
 }
 __global__ void __launch_bounds__(1024)
 tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sched, int slots, int cpb, int grade_big,
-                         int grade_small, int round_chunks) {
+                         int grade_small, int round_chunks, int short_per) {
   int32_t *used_of = sched + AT_SCHED_HDR + 4 * (int64_t)cfg.max_batch * AT_MAX_SLOTS;
+  // A list of under AT_GRADE_MIN_ROUNDS rounds is not graded; its one block size is chosen so that the blocks
+  // spread evenly over the CUs.  A CU streams at the same rate whether it holds two blocks or three, so a launch
+  // of equal blocks lasts as long as the CU with the most of them: with `per` chunks per block the list holds
+  // items(per) blocks per kv head, the fullest CU gets ceil(items / (CUs / kv_heads)) of them, and the launch
+  // takes that many times `per`.  (Measured after the flushes of the batch-64 workload, 64 working memories of
+  // 1.6-3.6K tokens on 256 CUs: blocks of 6 chunks, 4.2 per CU, run at 5.53 TB/s; of 4 chunks, 6.0 per CU: 5.79;
+  // of 3: 5.70; of 8: 5.36; whole sequences: 5.0-5.6.)  Where several sizes cost the same, sequences of one
+  // length take the largest (fewer partial results: 64 x 2,500 tokens, 102 us per launch whole against 104 in
+  // halves), unequal ones the smallest (the even spread the model assumes needs many small blocks: 5.76-5.79
+  // TB/s at 3 or 4 chunks against 5.53 at 6 in the measurement above, all three tied at 24 in the model).
+  __shared__ int s_items[2 * AT_MAX_CPB + 1];
+  __shared__ int s_per, s_cmin, s_cmax;
+  const int per_lo = max(cpb / 2, 1), per_hi = 2 * cpb, cu_items = max(round_chunks / cpb / AT_BLOCKS_PER_CU, 1);
+  for (int i = threadIdx.x; i <= 2 * AT_MAX_CPB; i += blockDim.x) s_items[i] = 0;
+  if (threadIdx.x == 0) {
+    s_cmin = INT32_MAX;
+    s_cmax = 0;
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
+    const int c = at_chunks_of(st.seq_len[b]);
+    if (c > 0) {
+      atomicMin(&s_cmin, c);
+      atomicMax(&s_cmax, c);
+    }
+    for (int per = per_lo; per <= per_hi; ++per) atomicAdd(&s_items[per], max(min(slots, (c + per - 1) / per), 1));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int best = cpb;
+    int64_t best_cost = INT64_MAX;
+    const bool equal_lengths = s_cmin >= s_cmax;
+    for (int per = per_lo; per <= per_hi; ++per) {
+      const int64_t cost = (int64_t)((s_items[per] + cu_items - 1) / cu_items) * per;
+      if (cost < best_cost || (cost == best_cost && equal_lengths)) {
+        best_cost = cost;
+        best = per;
+      }
+    }
+    s_per = short_per > 0 ? min(max(short_per, per_lo), per_hi) : best;
+  }
+  __syncthreads();
+  const int per_short = s_per;
   for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
     const int n = st.seq_len[b], c = at_chunks_of(n);
     int64_t work_before = 0, work_total = 0;
@@ -864,9 +908,10 @@ tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sch
       work_total += co;
       if (no > n || (no == n && o < b)) work_before += co;
     }
-    int per = cpb;
+    int per = per_short;
     const int64_t to_go = work_total - work_before;
     if (work_total >= (int64_t)AT_GRADE_MIN_ROUNDS * round_chunks) {
+      per = cpb;
       if (to_go * 16 > (int64_t)grade_big * round_chunks) per = 2 * cpb;
       else if (to_go * 16 <= (int64_t)grade_small * round_chunks) per = max(cpb / 2, 1);
     }
@@ -911,7 +956,8 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
   hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st, sched,
-                     ctx->sched_slots, ctx->sched_cpb, ctx->grade_big, ctx->grade_small, round_chunks > 0 ? round_chunks : 1);
+                     ctx->sched_slots, ctx->sched_cpb, ctx->grade_big, ctx->grade_small, round_chunks > 0 ? round_chunks : 1,
+                     ctx->short_per);
   TIM_LAUNCH_CHECK();
   ctx->sched_valid = true;
   return TIM_OK;

@@ -41,6 +41,7 @@ extern "C" int tim_ctx_get_tuning(const tim_ctx *ctx, tim_tuning *out) {
   out->grade_small = ctx->grade_small;
   out->round_items = ctx->round_items;
   out->block_waves = ctx->block_waves;
+  out->short_list_chunks = ctx->short_per;
   return TIM_OK;
 }
 
@@ -48,7 +49,8 @@ extern "C" int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *t) {
   if (!ctx || !t) return TIM_ERR_INVALID_ARG;
   if ((t->attn_impl != TIM_ATTN_VALU && t->attn_impl != TIM_ATTN_MFMA) || t->chunks_per_block < 1 ||
       t->chunks_per_block > 64 || t->fill < 1 || t->fill > 64 || t->grade_small < 0 || t->grade_big < t->grade_small ||
-      t->round_items < 0 || (t->block_waves != 0 && t->block_waves != 4 && t->block_waves != 6 && t->block_waves != 8 && t->block_waves != 12))
+      t->round_items < 0 || (t->block_waves != 0 && t->block_waves != 4 && t->block_waves != 6 && t->block_waves != 8 && t->block_waves != 12) ||
+      t->short_list_chunks < 0 || t->short_list_chunks > 128)
     return TIM_ERR_INVALID_ARG;
   ctx->attn_impl = t->attn_impl;
   ctx->attn_cpb = t->chunks_per_block;
@@ -57,6 +59,7 @@ extern "C" int tim_ctx_set_tuning(tim_ctx *ctx, const tim_tuning *t) {
   ctx->grade_small = t->grade_small;
   ctx->round_items = t->round_items;
   ctx->block_waves = t->block_waves;
+  ctx->short_per = t->short_list_chunks;
   ctx->sched_valid = false;  // a schedule written under the old shape no longer matches the launches
   return TIM_OK;
 }

@@ -23,6 +23,7 @@ struct tim_ctx {
   int attn_cpb;   // target chunks per attention block
   int attn_fill;  // shrink blocks until there are this many per CU
   int block_waves = 0;  // tim_tuning.block_waves: 0 = chosen per launch, else 4, 6, 8 or 12
+  int short_per = 0;    // tim_tuning.short_list_chunks: 0 = chosen by the schedule, else chunks per block of a list that is not graded
   double inv_freq[TIM_D / 2];  // theta_i in fp64, computed once on the host
   bool sched_valid = false;    // tim_attn_schedule ran and no call has changed a length since
   int sched_cpb = 0, sched_slots = 0, sched_waves = 4;

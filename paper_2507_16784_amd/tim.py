@@ -42,7 +42,7 @@ class tim_state(C.Structure):
 
 class tim_tuning(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("attn_impl", "chunks_per_block", "fill", "grade_big", "grade_small",
-                                         "round_items", "block_waves")]
+                                         "round_items", "block_waves", "short_list_chunks")]
 
 
 _PLAN_PTRS = ("seq_ids", "cover", "rank", "kept_idx", "new_pos", "delta", "src_slot", "dst_slot", "new_table",

@@ -47,13 +47,13 @@ def test_host_side_argument_checks_need_no_gpu():
     # launch-shape tuning is a host object: defaults, a round trip, and refused values
     t = tim.tim_tuning()
     assert lib.tim_ctx_get_tuning(h, ctypes.byref(t)) == tim.OK
-    assert (t.attn_impl, t.chunks_per_block, t.fill, t.grade_big, t.grade_small, t.round_items, t.block_waves) == (tim.ATTN_MFMA, 6, 2, 32, 8, 0, 0)
+    assert (t.attn_impl, t.chunks_per_block, t.fill, t.grade_big, t.grade_small, t.round_items, t.block_waves, t.short_list_chunks) == (tim.ATTN_MFMA, 6, 2, 32, 8, 0, 0, 0)
     t.chunks_per_block, t.round_items = 3, 4
     assert lib.tim_ctx_set_tuning(h, ctypes.byref(t)) == tim.OK
     t2 = tim.tim_tuning()
     assert lib.tim_ctx_get_tuning(h, ctypes.byref(t2)) == tim.OK and (t2.chunks_per_block, t2.round_items) == (3, 4)
     for field, bad_value in (("attn_impl", 2), ("chunks_per_block", 0), ("chunks_per_block", 65), ("fill", 0),
-                             ("grade_small", 33), ("grade_small", -1), ("round_items", -1), ("block_waves", 5)):
+                             ("grade_small", 33), ("grade_small", -1), ("round_items", -1), ("block_waves", 5), ("short_list_chunks", -1)):
         t3 = tim.tim_tuning()
         lib.tim_ctx_get_tuning(h, ctypes.byref(t3))
         setattr(t3, field, bad_value)
