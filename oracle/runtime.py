@@ -41,6 +41,7 @@ class Config:
     max_pages_per_seq: int
     max_nodes: int
     rope_base: float = 1.0e6
+    rope_pairing: int = 0          # rope.HALF_SPLIT or rope.INTERLEAVED
 
 
 class SeqPlan:
@@ -233,7 +234,7 @@ class OracleRuntime:
             for layer in range(layer_begin, layer_end):
                 self.v[layer, sp.dst_slot] = self.v[layer, sp.src_slot]
                 kb = self.k[layer, sp.src_slot]                     # [T, Hkv, D] bits
-                kr = rotate(bf16.to_f64(kb), sp.moved_delta[:, None], base)
+                kr = rotate(bf16.to_f64(kb), sp.moved_delta[:, None], base, self.cfg.rope_pairing)
                 out = bf16.from_f64(kr)
                 still = sp.moved_delta == 0                       # unmoved position: bit copy
                 out[still] = kb[still]

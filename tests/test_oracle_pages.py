@@ -5,7 +5,7 @@ import pytest
 from oracle import bf16
 from oracle.attention import attend
 from oracle.pages import FreeStack
-from oracle.rope import rotate
+from oracle.rope import HALF_SPLIT, INTERLEAVED, rotate as _rotate
 from oracle.runtime import (ERR_OOM_PAGES, MARK_CLOSE, MARK_OPEN, MARK_SUB_BEGIN, MARK_SUB_END, Config,
                             OracleRuntime)
 
@@ -124,14 +124,17 @@ def test_pool_exhaustion_fails_as_a_whole():
     assert rt.buffers[0].pending == [0]
 
 
-def test_compacted_cache_attends_like_rope_at_the_new_positions():
-    """End to end on one sequence: keys are stored rotated at their old positions; after
+@pytest.mark.parametrize("pairing", [HALF_SPLIT, INTERLEAVED])
+def test_compacted_cache_attends_like_rope_at_the_new_positions(pairing):
+    """End to end on one sequence, for both rotary pairings (a runtime that ignored its configuration's
+    pairing would fail the second): keys are stored rotated at their old positions; after
     a flush, attention over the compacted, re-rotated cache with a query rotated at the new
     position equals attention built from the unrotated keys of the survivors placed at
     positions 0..m-1 (up to the two bf16 roundings of the stored keys)."""
     rng = np.random.default_rng(0)
+    rotate = lambda x, pos, base: _rotate(x, pos, base, pairing)
     cfg = Config(layers=1, q_heads=4, kv_heads=1, head_dim=128, page_size=16, num_pages=16, max_batch=1,
-                 max_pages_per_seq=8, max_nodes=4)
+                 max_pages_per_seq=8, max_nodes=4, rope_pairing=pairing)
     rt = OracleRuntime(cfg, 0)
     n = 70
     k_raw = rng.standard_normal((n, 1, 128))
@@ -225,7 +228,7 @@ def test_page_size_one_keeps_survivor_pages_and_returns_the_rest_in_order():
         if t == 8:
             rt.mark([(0, MARK_SUB_END, 0, -1)])
         rt.advance()
-        rt.append(0, bf16.from_f64(rotate(raw[t], np.array([t]), 1.0e6))[None], bf16.from_f64(raw[t])[None])
+        rt.append(0, bf16.from_f64(_rotate(raw[t], np.array([t]), 1.0e6))[None], bf16.from_f64(raw[t])[None])
     assert list(rt.page_table[0, :12]) == list(range(12)) and list(rt.free.free_ids()) == [15, 14, 13, 12]
     k_before, v_before = rt.gather_kv(0, 0)
     ev = rt.prune_plan([0])
@@ -238,8 +241,8 @@ def test_page_size_one_keeps_survivor_pages_and_returns_the_rest_in_order():
     k_after, v_after = rt.gather_kv(0, 0)
     assert np.array_equal(v_after, v_before[[0, 1, 2, 8, 9, 10, 11]])
     assert np.array_equal(k_after[:3], k_before[:3])
-    want = bf16.from_f64(rotate(bf16.to_f64(k_before[8:12]), np.full((4, 1), -5), 1.0e6))
+    want = bf16.from_f64(_rotate(bf16.to_f64(k_before[8:12]), np.full((4, 1), -5), 1.0e6))
     assert np.array_equal(k_after[3:], want)
-    exact = rotate(raw[8:12], np.arange(3, 7)[:, None], 1.0e6)          # keys placed directly at 3..6
+    exact = _rotate(raw[8:12], np.arange(3, 7)[:, None], 1.0e6)          # keys placed directly at 3..6
     assert np.max(np.abs(bf16.to_f64(k_after[3:]) - exact)) < 2.0 ** -6 * np.max(np.abs(exact))
     _check_conservation(rt)
