@@ -75,7 +75,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, page_size=16):
+def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, page_size=16, rope_pairing=0):
     import numpy as np
     from paper_2507_16784_amd.workload.state import scattered_pages
 
@@ -102,7 +102,7 @@ def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, pag
         k_pool[l].normal_(0.0, shape.kv_scale, generator=g)
         v_pool[l].normal_(0.0, shape.kv_scale, generator=g)
     ctx = tim.Context(L, shape.q_heads, shape.kv_heads, num_pages, B, mp, max_nodes, page_size=ps,
-                      pools=(k_pool, v_pool))
+                      pools=(k_pool, v_pool), rope_pairing=rope_pairing)
     tables, free_ids = scattered_pages(seed, num_pages, ps, wl.preload)
     pt = np.full((B, mp), -1, dtype=np.int32)
     for b, t in enumerate(tables):
@@ -258,7 +258,7 @@ def flush_mode(torch, tim, np, ctx, plan, shape, wl, initial, args):
         "value": round(float(np.median(t_plan)) + ms_c + float(np.median(t_commit)), 3), "unit": "ms per flush call",
         "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name + "/all-big-flushes", "batch": B, "layers": ctx.cfg.layers, "page_size": ps,
-                   "tokens_before": n_before, "tokens_after": n_after, "prune_ratio": round(1 - n_after / n_before, 4),
+                   "rope_pairing": "interleaved" if ctx.cfg.rope_pairing else "half-split", "tokens_before": n_before, "tokens_after": n_after, "prune_ratio": round(1 - n_after / n_before, 4),
                    "moved_tokens": moved},
         "plan_ms": round(float(np.median(t_plan)), 3), "compact_ms": round(ms_c, 3),
         "commit_ms": round(float(np.median(t_commit)), 3),
@@ -510,6 +510,8 @@ def main():
                          "the kernel-level roofline pass still runs eagerly")
     ap.add_argument("--page-size", type=int, default=16, choices=[16, 1],
                     help="16 (default) or 1, the paper's own page size: flushes then move no rows")
+    ap.add_argument("--rope-pairing", default="half-split", choices=["half-split", "interleaved"],
+                    help="rotary pairing the compaction re-rotates by (window and flush modes); the configurations use half-split")
     ap.add_argument("--tune", default="",
                     help="A/B measurements: fields of tim_tuning to override, e.g. block_waves=6,chunks_per_block=8")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -560,7 +562,8 @@ def main():
     args.warmup = min(args.warmup, args.steps)
     shape.q_scale = 128 ** -0.5
     ctx, L_alloc = build_context(torch, tim, shape, wl, headroom_pages=headroom, layers_alloc=args.layers_alloc,
-                                 seed=args.seed, page_size=args.page_size)
+                                 seed=args.seed, page_size=args.page_size,
+                                 rope_pairing=1 if args.rope_pairing == "interleaved" else 0)
     if args.tune:
         ctx.tim_ctx_set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     plan = tim.Plan(ctx.cfg, args.batch)

@@ -26,13 +26,13 @@
  *     One context serves one stream at a time.
  *   - Shapes: head_dim = 128, q_heads = 4 * kv_heads, page_size = 16, or 1 (the paper's
  *     own setting, Sec. 3.1; see "Page size 1" below).  Other values are rejected with
- *     TIM_ERR_INVALID_ARG.  One pool layout (below) and one rotary pairing (half-split).
+ *     TIM_ERR_INVALID_ARG.  One pool layout (below); the rotary pairing is a field of tim_config.
  *   - bf16 is the upper half of an IEEE binary32, round-to-nearest-even.
  *
  * Data layout
  *   K and V pools: bf16 [layers][num_pages][kv_heads][page_size][head_dim],
  *   so the 16 rows of one (page, kv head) are 4 KiB contiguous.  Keys are
- *   stored rotated (RoPE, pairs (i, i + 64), theta_i = rope_base^(-2i/128)) at
+ *   stored rotated (RoPE, pairs per tim_config.rope_pairing, theta_i = rope_base^(-2i/128)) at
  *   their current position.  A token with logical index t of sequence b lives
  *   in page page_table[b][t / 16], row t % 16.  "slot" = page * 16 + row.
  *
@@ -81,6 +81,14 @@ typedef enum {
 
 typedef enum { TIM_OUT_F32 = 0, TIM_OUT_BF16 = 1 } tim_out_dtype;
 
+/* Which two coordinates of a key row turn together under the rotary embedding (the position
+ * reassignment of Sec. 3.1 / Eq. 1 is done by turning each kept key by its position change).
+ * Pair i turns by (change) * rope_base^(-2i/128) in both; only tim_kv_compact reads it. */
+typedef enum {
+  TIM_ROPE_HALF_SPLIT = 0,  /* pair i = (i, i + 64): the base model's family */
+  TIM_ROPE_INTERLEAVED = 1  /* pair i = (2i, 2i + 1): the original rotary formulation */
+} tim_rope_pairing;
+
 typedef struct {
   int32_t layers;
   int32_t q_heads;
@@ -92,6 +100,7 @@ typedef struct {
   int32_t max_pages_per_seq; /* row length of page_table */
   int32_t max_nodes;         /* task-tree nodes per sequence */
   float rope_base;           /* 1e6 in the configurations */
+  int32_t rope_pairing;      /* tim_rope_pairing; TIM_ROPE_HALF_SPLIT in the configurations */
 } tim_config;
 
 /* Caller-owned device buffers that make up one decoding context. */

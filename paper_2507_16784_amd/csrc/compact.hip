@@ -10,6 +10,10 @@
 // thread (angle in fp64, reduced to [-pi, pi], then fp32 sincos) and reused for every
 // head and layer of the group, which keeps the kernel on the bandwidth roof.
 //
+// With the interleaved pairing (pairs (2i, 2i+1)) the same thread owns the same two pieces; each 32-bit word then
+// is one pair, the first piece holds pairs 4c..4c+3 and the second pairs 32+4c..32+4c+3, and only the angles and
+// the arithmetic between registers differ (template parameter IL): addresses and traffic are the same.
+//
 // No tile passes through LDS: a thread holds both halves of its rotation pairs in registers, so there is nothing
 // to exchange.  A variant that did stage the key tile through LDS (256 threads per page, whole 256-byte rows per 16
 // lanes on the way in, the 4 KiB destination tile written linearly, the partner half read from LDS under an XOR
@@ -32,13 +36,62 @@ __device__ __forceinline__ uint32_t bf_pack(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
+// cos / sin of the thread's eight angles for a position change d.  Half-split: pairs 8c..8c+7 (theta_step =
+// theta_8).  Interleaved: pairs 4c..4c+3, then 32+4c..32+4c+3 (theta_step = theta_4).  theta_i is built by fp64
+// multiplication from theta_1 (relative error ~1e-15, far below the fp32 sincos); the angle is reduced to
+// [-pi, pi] in fp64 with a two-term 2 pi.
+template <bool IL>
+__device__ __forceinline__ void cp_angles(int d, int c, double theta1, double theta_step, double theta32, float (&cs)[8],
+                                          float (&sn)[8]) {
+  double th0 = 1.0;
+  for (int q = 0; q < c; ++q) th0 *= theta_step;
+  const double two_pi_hi = 6.283185307179586232e+00, two_pi_lo = 2.449293598294706414e-16;
+  const double inv_two_pi = 1.591549430918953456e-01;
+  double th = th0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    if (IL && k == 4) th = th0 * theta32;
+    const double a = (double)d * th;
+    const double n2 = rint(a * inv_two_pi);
+    double r = fma(-n2, two_pi_hi, a);
+    r = fma(-n2, two_pi_lo, r);
+    sincosf((float)r, &sn[k], &cs[k]);
+    th *= theta1;
+  }
+}
+
+// Rotates the thread's two 16-byte pieces of one key row (lo = dims 8c..8c+7, hi = the same + 64) in fp32.
+template <bool IL>
+__device__ __forceinline__ void cp_rotate(uint4 &lo, uint4 &hi, const float (&cs)[8], const float (&sn)[8]) {
+  uint32_t *a = reinterpret_cast<uint32_t *>(&lo);
+  uint32_t *b = reinterpret_cast<uint32_t *>(&hi);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (IL) {  // each word is a pair: (dims 8c+2w, 8c+2w+1) in lo, the same + 64 in hi
+      const float x = bf_lo(a[w]), y = bf_hi(a[w]);
+      const float u = bf_lo(b[w]), v = bf_hi(b[w]);
+      a[w] = bf_pack(fmaf(x, cs[w], -(y * sn[w])), fmaf(y, cs[w], x * sn[w]));
+      b[w] = bf_pack(fmaf(u, cs[4 + w], -(v * sn[4 + w])), fmaf(v, cs[4 + w], u * sn[4 + w]));
+    } else {
+      const float x0 = bf_lo(a[w]), x1 = bf_hi(a[w]);  // dims 8c+2w, 8c+2w+1
+      const float y0 = bf_lo(b[w]), y1 = bf_hi(b[w]);  // their partners at +64
+      const float c0 = cs[2 * w], s0 = sn[2 * w], c1 = cs[2 * w + 1], s1 = sn[2 * w + 1];
+      const float rx0 = fmaf(x0, c0, -(y0 * s0)), ry0 = fmaf(y0, c0, x0 * s0);
+      const float rx1 = fmaf(x1, c1, -(y1 * s1)), ry1 = fmaf(y1, c1, x1 * s1);
+      a[w] = bf_pack(rx0, rx1);
+      b[w] = bf_pack(ry0, ry1);
+    }
+  }
+}
+
 // Work items are (destination page, layer group) pairs.  The destination pages of a flush
 // are exactly its fresh pages, numbered 0..total_need-1 in (sequence, page) order, so item
 // i belongs to the sequence whose PAGE_OFF range contains i; no work list is materialised
 // and the host never needs to know how much moved: a fixed grid strides over the items.
+template <bool IL>
 __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const tim_state &st, const tim_plan &pl,
                                                  int n_seqs, int item, int l0, int l1, double theta1,
-                                                 double theta8) {
+                                                 double theta_step, double theta32) {
   // sequence of this fresh page: last e with PAGE_OFF[e] <= item (n_seqs is small)
   int lo = 0, hi = n_seqs - 1;
   while (lo < hi) {
@@ -63,21 +116,7 @@ __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const ti
   }
 
   float cs[8], sn[8];
-  if (d != 0) {
-    double th = 1.0;
-    for (int q = 0; q < c; ++q) th *= theta8;  // theta_{8c}
-    const double two_pi_hi = 6.283185307179586232e+00, two_pi_lo = 2.449293598294706414e-16;
-    const double inv_two_pi = 1.591549430918953456e-01;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const double a = (double)d * th;
-      const double n2 = rint(a * inv_two_pi);
-      double r = fma(-n2, two_pi_hi, a);
-      r = fma(-n2, two_pi_lo, r);
-      sincosf((float)r, &sn[k], &cs[k]);
-      th *= theta1;
-    }
-  }
+  if (d != 0) cp_angles<IL>(d, c, theta1, theta_step, theta32, cs, sn);
 
   const uint4 *kp = reinterpret_cast<const uint4 *>(st.k_pool);
   const uint4 *vp = reinterpret_cast<const uint4 *>(st.v_pool);
@@ -108,20 +147,7 @@ __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const ti
       }
       if (d != 0) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          uint32_t *a = reinterpret_cast<uint32_t *>(&klo[u]);
-          uint32_t *b = reinterpret_cast<uint32_t *>(&khi[u]);
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const float x0 = bf_lo(a[w]), x1 = bf_hi(a[w]);  // dims 8c+2w, 8c+2w+1
-            const float y0 = bf_lo(b[w]), y1 = bf_hi(b[w]);  // their partners at +64
-            const float c0 = cs[2 * w], s0 = sn[2 * w], c1 = cs[2 * w + 1], s1 = sn[2 * w + 1];
-            const float rx0 = fmaf(x0, c0, -(y0 * s0)), ry0 = fmaf(y0, c0, x0 * s0);
-            const float rx1 = fmaf(x1, c1, -(y1 * s1)), ry1 = fmaf(y1, c1, x1 * s1);
-            a[w] = bf_pack(rx0, rx1);
-            b[w] = bf_pack(ry0, ry1);
-          }
-        }
+        for (int u = 0; u < 2; ++u) cp_rotate<IL>(klo[u], khi[u], cs, sn);
       }
       tim_store_stream(kw + dof, klo[0]);
       tim_store_stream(kw + dof + 8, khi[0]);
@@ -137,16 +163,18 @@ __device__ __forceinline__ void tim_compact_item(const tim_config &cfg, const ti
   }
 }
 
+template <bool IL>
 __global__ void __launch_bounds__(CP_THREADS)
 tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer_begin, int layer_end,
-                   double theta1, double theta8) {
+                   double theta1, double theta_step, double theta32) {
   if (!pl.totals[TIM_TOT_OK]) return;
   const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
   const int64_t n_work = (int64_t)pl.totals[TIM_TOT_NEED] * groups;
   for (int64_t w = blockIdx.x; w < n_work; w += gridDim.x) {
     const int item = (int)(w / groups), grp = (int)(w % groups);
     const int l0 = layer_begin + grp * CP_LAYERS_PER_BLOCK;
-    tim_compact_item(cfg, st, pl, n_seqs, item, l0, min(l0 + CP_LAYERS_PER_BLOCK, layer_end), theta1, theta8);
+    tim_compact_item<IL>(cfg, st, pl, n_seqs, item, l0, min(l0 + CP_LAYERS_PER_BLOCK, layer_end), theta1, theta_step,
+                         theta32);
   }
 }
 
@@ -155,9 +183,10 @@ tim_compact_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int la
 // per token per layer instead of 2 x 4 KiB, values untouched).  Work items are (tile of 32
 // such tokens, layer group); thread (t, c) owns token t's eight rotation pairs as above and
 // reads and writes the same addresses, so there is no hazard between threads.
+template <bool IL>
 __global__ void __launch_bounds__(CP_THREADS)
 tim_rotate_inplace_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs, int layer_begin, int layer_end,
-                          double theta1, double theta8) {
+                          double theta1, double theta_step, double theta32) {
   if (!pl.totals[TIM_TOT_OK]) return;
   const int groups = (layer_end - layer_begin + CP_LAYERS_PER_BLOCK - 1) / CP_LAYERS_PER_BLOCK;
   const int64_t n_work = (int64_t)pl.totals[TIM_TOT_EXT_TILES] * groups;
@@ -189,19 +218,7 @@ tim_rotate_inplace_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs,
         continue;
       }
       float cs[8], sn[8];
-      double th = 1.0;
-      for (int q = 0; q < c; ++q) th *= theta8;
-      const double two_pi_hi = 6.283185307179586232e+00, two_pi_lo = 2.449293598294706414e-16;
-      const double inv_two_pi = 1.591549430918953456e-01;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const double a = (double)d * th;
-        const double n2 = rint(a * inv_two_pi);
-        double r = fma(-n2, two_pi_hi, a);
-        r = fma(-n2, two_pi_lo, r);
-        sincosf((float)r, &sn[k], &cs[k]);
-        th *= theta1;
-      }
+      cp_angles<IL>(d, c, theta1, theta_step, theta32, cs, sn);
       for (int layer = l0; layer < l1; ++layer) {
         const int64_t base = (((int64_t)layer * cfg.num_pages + slot) * hkv) * 16 + c;  // uint4 units, row = 16
         for (int h = 0; h < hkv; h += 2) {
@@ -213,21 +230,8 @@ tim_rotate_inplace_kernel(tim_config cfg, tim_state st, tim_plan pl, int n_seqs,
             klo[1] = kw[base + (int64_t)(h + 1) * 16];
             khi[1] = kw[base + (int64_t)(h + 1) * 16 + 8];
           }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            uint32_t *a = reinterpret_cast<uint32_t *>(&klo[u]);
-            uint32_t *b = reinterpret_cast<uint32_t *>(&khi[u]);
-#pragma unroll
-            for (int wd = 0; wd < 4; ++wd) {
-              const float x0 = bf_lo(a[wd]), x1 = bf_hi(a[wd]);
-              const float y0 = bf_lo(b[wd]), y1 = bf_hi(b[wd]);
-              const float c0 = cs[2 * wd], s0 = sn[2 * wd], c1 = cs[2 * wd + 1], s1 = sn[2 * wd + 1];
-              const float rx0 = fmaf(x0, c0, -(y0 * s0)), ry0 = fmaf(y0, c0, x0 * s0);
-              const float rx1 = fmaf(x1, c1, -(y1 * s1)), ry1 = fmaf(y1, c1, x1 * s1);
-              a[wd] = bf_pack(rx0, rx1);
-              b[wd] = bf_pack(ry0, ry1);
-            }
-          }
+          cp_rotate<IL>(klo[0], khi[0], cs, sn);
+          if (two) cp_rotate<IL>(klo[1], khi[1], cs, sn);
           kw[base + (int64_t)h * 16] = klo[0];
           kw[base + (int64_t)h * 16 + 8] = khi[0];
           if (two) {
@@ -249,14 +253,12 @@ extern "C" int tim_kv_compact(tim_ctx *ctx, const tim_plan *plan, int32_t layer_
   if (layer_begin == layer_end) return TIM_OK;
   // enough two-wave blocks to keep every CU's load queues full; they stride over the items
   dim3 grid(16 * ctx->n_cu);
-  if (ctx->cfg.page_size == 1) {
-    hipLaunchKernelGGL(tim_rotate_inplace_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
-                       plan->n_seqs, layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
-    TIM_LAUNCH_CHECK();
-    return TIM_OK;
-  }
-  hipLaunchKernelGGL(tim_compact_kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,
-                     plan->n_seqs, layer_begin, layer_end, ctx->inv_freq[1], ctx->inv_freq[8]);
+  const bool il = ctx->cfg.rope_pairing == TIM_ROPE_INTERLEAVED;
+  const double theta1 = ctx->inv_freq[1], theta_step = ctx->inv_freq[il ? 4 : 8], theta32 = ctx->inv_freq[32];
+  auto kernel = ctx->cfg.page_size == 1 ? (il ? tim_rotate_inplace_kernel<true> : tim_rotate_inplace_kernel<false>)
+                                        : (il ? tim_compact_kernel<true> : tim_compact_kernel<false>);
+  hipLaunchKernelGGL(kernel, grid, dim3(CP_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan, plan->n_seqs,
+                     layer_begin, layer_end, theta1, theta_step, theta32);
   TIM_LAUNCH_CHECK();
   return TIM_OK;
 }

@@ -9,7 +9,8 @@ extern "C" int tim_ctx_create(tim_ctx **out, const tim_config *cfg) {
   *out = nullptr;
   if (cfg->head_dim != TIM_D || (cfg->page_size != TIM_PS && cfg->page_size != 1) || cfg->kv_heads <= 0 ||
       cfg->q_heads != TIM_G * cfg->kv_heads || cfg->layers <= 0 || cfg->num_pages <= 0 || cfg->max_batch <= 0 ||
-      cfg->max_pages_per_seq <= 0 || cfg->max_nodes <= 0 || !(cfg->rope_base > 1.0f))
+      cfg->max_pages_per_seq <= 0 || cfg->max_nodes <= 0 || !(cfg->rope_base > 1.0f) ||
+      (cfg->rope_pairing != TIM_ROPE_HALF_SPLIT && cfg->rope_pairing != TIM_ROPE_INTERLEAVED))
     return TIM_ERR_INVALID_ARG;
   // slots are int32: page * 16 + row must not overflow
   if ((int64_t)cfg->num_pages * cfg->page_size > INT32_MAX || (int64_t)cfg->max_pages_per_seq * cfg->page_size > INT32_MAX / 2)

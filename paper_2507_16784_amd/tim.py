@@ -30,7 +30,8 @@ EXPORTS = ["tim_attn_ws_bytes", "tim_ctx_create", "tim_ctx_destroy", "tim_bind",
 
 class tim_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("layers", "q_heads", "kv_heads", "head_dim", "page_size", "num_pages",
-                                         "max_batch", "max_pages_per_seq", "max_nodes")] + [("rope_base", C.c_float)]
+                                         "max_batch", "max_pages_per_seq", "max_nodes")] + [("rope_base", C.c_float),
+                                                                                            ("rope_pairing", C.c_int32)]
 
 
 class tim_state(C.Structure):
@@ -149,9 +150,10 @@ class Context:
     """One decoding context: owns the torch device buffers of tim_state and the tim_ctx handle."""
 
     def __init__(self, layers, q_heads, kv_heads, num_pages, max_batch, max_pages_per_seq, max_nodes,
-                 head_dim=128, page_size=16, rope_base=1.0e6, device="cuda", pools=None, workspace=True):
+                 head_dim=128, page_size=16, rope_base=1.0e6, device="cuda", pools=None, workspace=True,
+                 rope_pairing=0):
         self.cfg = tim_config(layers, q_heads, kv_heads, head_dim, page_size, num_pages, max_batch,
-                              max_pages_per_seq, max_nodes, rope_base)
+                              max_pages_per_seq, max_nodes, rope_base, rope_pairing)
         self.handle = C.c_void_p()
         _check(lib().tim_ctx_create(C.byref(self.handle), C.byref(self.cfg)), "tim_ctx_create")
         i32 = dict(dtype=torch.int32, device=device)

@@ -32,7 +32,8 @@ class GpuRuntime:
         self.cfg = cfg
         self.threshold = threshold
         self.ctx = tim.Context(cfg.layers, cfg.q_heads, cfg.kv_heads, cfg.num_pages, cfg.max_batch,
-                               cfg.max_pages_per_seq, cfg.max_nodes, cfg.head_dim, cfg.page_size, cfg.rope_base)
+                               cfg.max_pages_per_seq, cfg.max_nodes, cfg.head_dim, cfg.page_size, cfg.rope_base,
+                               rope_pairing=cfg.rope_pairing)
         self.ctx.tim_ctx_set_tuning(**(dict(round_items=4) if tuning is None else tuning))
         self.plan = tim.Plan(self.ctx.cfg, max_flush_seqs or cfg.max_batch)
         self.dev = self.ctx.seq_len.device

@@ -10,7 +10,7 @@ from paper_2507_16784_amd.workload.state import scattered_pages
 
 
 def make_config(wl, layers, q_heads, kv_heads, headroom_pages, max_nodes=None, head_dim=128,
-                page_size=16, max_pages_per_seq=None, rope_base=1.0e6):
+                page_size=16, max_pages_per_seq=None, rope_base=1.0e6, rope_pairing=0):
     b = len(wl.traces)
     longest = max(p0 + wl.steps for p0 in wl.preload)
     mp = max_pages_per_seq or (longest + page_size - 1) // page_size + 1
@@ -18,7 +18,7 @@ def make_config(wl, layers, q_heads, kv_heads, headroom_pages, max_nodes=None, h
     return Config(layers=layers, q_heads=q_heads, kv_heads=kv_heads, head_dim=head_dim,
                   page_size=page_size, num_pages=used + headroom_pages, max_batch=b,
                   max_pages_per_seq=mp, max_nodes=max_nodes or max(1, max(t.n_nodes for t in wl.traces)),
-                  rope_base=rope_base)
+                  rope_base=rope_base, rope_pairing=rope_pairing)
 
 
 def preload_oracle(rt: OracleRuntime, wl, seed: int, kv_scale: float, tag_values=False):

@@ -34,6 +34,8 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(bad)) == tim.ERR_INVALID_ARG
     bad = tim.tim_config(1, 6, 2, 128, 16, 8, 1, 4, 4, 1.0e6)         # group size 3 is unsupported
     assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(bad)) == tim.ERR_INVALID_ARG
+    bad = tim.tim_config(1, 8, 2, 128, 16, 8, 1, 4, 4, 1.0e6, 2)       # neither rotary pairing
+    assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(bad)) == tim.ERR_INVALID_ARG
     ok = tim.tim_config(1, 8, 2, 128, 16, 8, 1, 4, 4, 1.0e6)
     assert lib.tim_ctx_create(ctypes.byref(h), ctypes.byref(ok)) == tim.OK
     # unbound context: every stream call is refused before anything is launched

@@ -86,13 +86,20 @@ def check_state(ora, gpu):
     assert stats[1] == stats[2] == ora.pages_in_use() and stats[3] == 0      # no entry beyond a length, no page twice
 
 
-def check_rotated(kg, ko):
+def pair_norm(f, pairing=0):
+    """Per coordinate, the norm of the rotation pair it belongs to (pairing: the oracle Config's rope_pairing)."""
+    if pairing == 0:
+        norm = np.hypot(f[..., :64], f[..., 64:])
+        return np.concatenate([norm, norm], axis=-1)
+    return np.repeat(np.hypot(f[..., 0::2], f[..., 1::2]), 2, axis=-1)
+
+
+def check_rotated(kg, ko, pairing=0):
     """Re-rotated keys against the oracle's float64 result from the same stored input."""
     steps = bf16_steps(kg, ko)
     if steps.max(initial=0) > 0:
         fo, fg = bf16.to_f64(ko), bf16.to_f64(kg)
-        norm = np.hypot(fo[..., :64], fo[..., 64:])
-        norm = np.concatenate([norm, norm], axis=-1)
+        norm = pair_norm(fo, pairing)
         one_step = np.maximum(np.abs(fo), 2.0 ** -126) * 2.0 ** -7
         assert np.all(np.abs(fg - fo) <= one_step + 2.0 ** -20 * norm)
     return steps.size, int((steps == 0).sum())
@@ -113,9 +120,9 @@ def check_event_kv(ora, gpu, ev, before):
             assert np.array_equal(vg, vb[pl.kept_idx])
             still = pl.delta == 0
             assert np.array_equal(kg[still], kb[pl.kept_idx[still]])
-            want = bf16.from_f64(rotate(bf16.to_f64(kb[pl.kept_idx]), pl.delta[:, None], c.rope_base))
+            want = bf16.from_f64(rotate(bf16.to_f64(kb[pl.kept_idx]), pl.delta[:, None], c.rope_base, c.rope_pairing))
             want[still] = kb[pl.kept_idx[still]]
-            n, k = check_rotated(kg, want)
+            n, k = check_rotated(kg, want, c.rope_pairing)
             tot += n
             same += k
     assert same >= 0.99 * tot
@@ -136,14 +143,12 @@ def check_kv(ora, gpu, drift_ok=False, oracle_is_ahead=False):
             assert np.array_equal(vg, vo)                               # values: bit copies
             if drift_ok:
                 fo, fg = bf16.to_f64(ko), bf16.to_f64(kg)
-                norm = np.hypot(fo[..., :64], fo[..., 64:])
-                norm = np.concatenate([norm, norm], axis=-1)
-                assert np.all(np.abs(fg - fo) <= 2.0 ** -6 * norm + 1e-30)
+                assert np.all(np.abs(fg - fo) <= 2.0 ** -6 * pair_norm(fo, c.rope_pairing) + 1e-30)
                 st = bf16_steps(kg, ko)
                 tot += st.size
                 same += int((st == 0).sum())
             else:
-                n, k = check_rotated(kg, ko)
+                n, k = check_rotated(kg, ko, c.rope_pairing)
                 tot += n
                 same += k
     assert same >= 0.99 * tot
@@ -241,7 +246,8 @@ def test_config4_prune_heavy_recycling(gb):
 def test_seeded_shape_sweep(gb, case):
     """Shapes no other test fixes by hand: head counts that are not powers of two, layer counts
     that are not multiples of the compaction kernel's layer group, odd batches, both page sizes,
-    both rotary bases, tight and roomy page tables, fused and separate append - drawn from a seed."""
+    both rotary bases, both rotary pairings, tight and roomy page tables, fused and separate append - drawn
+    from a seed."""
     rng = np.random.RandomState(1000 + case)
     kv_heads = int(rng.choice([1, 2, 3, 5, 8]))
     layers = int(rng.choice([1, 2, 3, 5]))
@@ -259,7 +265,7 @@ def test_seeded_shape_sweep(gb, case):
     cfg = harness.make_config(wl, layers=layers, q_heads=4 * kv_heads, kv_heads=kv_heads,
                               headroom_pages=int(rng.randint(4, 40)) * (16 // page_size) * batch, page_size=page_size,
                               max_pages_per_seq=tight if rng.randint(2) else tight + int(rng.randint(1, 40)),
-                              rope_base=float(rng.choice([1.0e4, 1.0e6])))
+                              rope_base=float(rng.choice([1.0e4, 1.0e6])), rope_pairing=(case // 2) % 2)
     kv_scale = float(rng.choice([1.0, 128 ** -0.5]))
     sm_scale = float(rng.choice([128 ** -0.5, 0.02, 0.3]))
     replay(gb, wl, cfg, threshold, 3000 + case, kv_scale, sm_scale, attend_every=int(rng.randint(1, 4)),
@@ -845,6 +851,35 @@ def test_page_size_one_small_events(gb, threshold, cadence):
     wl = Workload(traces, p0s, steps, every(cadence, steps, 3))
     cfg = harness.make_config(wl, layers=2, q_heads=8, kv_heads=2, headroom_pages=400, page_size=1)
     replay(gb, wl, cfg, threshold, 6, 1.0, 128 ** -0.5)
+
+
+@pytest.mark.parametrize("page_size", [16, 1])
+def test_interleaved_rotary_pairing(gb, page_size):
+    """tim_config.rope_pairing = interleaved (pairs 2i, 2i+1): every flush of a busy small batch (3 layers,
+    so the compaction kernel's layer group is ragged) and one flush at configuration-1 size with 32 / 8
+    heads are re-rotated as the oracle's interleaved rotation does it; check_event_kv holds each moved key
+    to one bf16 step of the float64 result and 99 % of them to the same bits, which the half-split
+    arithmetic applied to the same rows does not meet."""
+    seeds, p0s, steps = [81, 82, 83], [37, 64, 150], 60
+    traces = [generate(s, p + steps + 1, SPEC_TINY) for s, p in zip(seeds, p0s)]
+    wl = Workload(traces, p0s, steps, every(3, steps, 3))
+    cfg = harness.make_config(wl, layers=3, q_heads=8, kv_heads=2, headroom_pages=40 * (16 // page_size) * 3,
+                              page_size=page_size, rope_pairing=1)
+    replay(gb, wl, cfg, 1, 8, 1.0, 128 ** -0.5, attend_every=5)
+    p0, steps = 4096, 2
+    wl = Workload([generate(2, p0 + steps + 1, SPEC_C1)], [p0], steps, {0: [0]})
+    cfg = harness.make_config(wl, layers=1, q_heads=32, kv_heads=8, headroom_pages=300 * (16 // page_size),
+                              page_size=page_size, rope_base=1.0e4, rope_pairing=1)
+    ora, _ = replay(gb, wl, cfg, 1, 2, 128 ** -0.5, 128 ** -0.5)
+    assert ora.seq_len[0] < p0
+    # the two conventions really differ on this input: the oracle's half-split rotation of the same flush
+    # does not pass the gate the GPU result just passed
+    k = bf16.from_f64(np.random.default_rng(0).standard_normal((64, 2, 128)))
+    d = -np.arange(1, 65)[:, None]
+    a = bf16.from_f64(rotate(bf16.to_f64(k), d, 1.0e4, 1))
+    b = bf16.from_f64(rotate(bf16.to_f64(k), d, 1.0e4, 0))
+    with pytest.raises(AssertionError):
+        check_rotated(b, a, 1)
 
 
 def test_page_size_one_config1_and_config2_shapes(gb):
