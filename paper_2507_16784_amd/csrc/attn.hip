@@ -689,10 +689,14 @@ tim_attn_partial_mfma_kernel(tim_config cfg, tim_state st, AttnWs ws, int layer,
     }
   };
 
-  // (Requesting a wave's next pair before working on the current one, with two register sets that swap roles,
-  // was measured and rejected: at 256 registers the compiler spills about 50 of them inside the loop and a CU
-  // holds 8 waves instead of 12: 35.4 against 50.5 decode steps/s on long working memories, 37.8 against 26.1 us
-  // per launch on short ones.)
+  // (Requesting a wave's next pair before working on the current one was measured twice and rejected.  With two
+  // register sets that swap roles the compiler spills about 50 of 256 registers inside the loop and a CU holds 8
+  // waves instead of 12: 35.4 against 50.5 decode steps/s on long working memories, 37.8 against 26.1 us per
+  // launch on short ones.  At 12 waves per CU, with the next pair's V tiles copied straight into a per-wave LDS
+  // stage and its K tiles loaded into the registers the score products have just freed (no extra registers, both
+  // requests in flight during the weights and output products): 50.79 against 50.60 steps/s on long working
+  // memories, 1,005 against 1,017 on short ones in a small batch, same box, alternating.  Twelve waves per CU
+  // already keep the memory system as busy as it gets; the wave's own wait is not what limits the kernel.)
   int k = 0;
   for (int pr = unit; pr < n_pairs; pr += stride, ++k) {
     advance_ids(pr, k);
