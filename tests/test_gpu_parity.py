@@ -390,6 +390,46 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
     assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("short_list_chunks", [0, 1, 4, 7, 128])
+def test_block_size_of_a_list_too_short_to_grade(gb, short_list_chunks):
+    """tim_attn_schedule on a batch after its flushes (a list of under three rounds of work): one block size for
+    the whole list, chosen from the lengths (0) or fixed by tim_tuning.short_list_chunks (clamped to
+    chunks_per_block / 2 .. x 2); results against the oracle for fp32 and bf16 output, and the work
+    list itself: every sequence cut into ceil(chunks / size) blocks for one common size."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    from oracle import attention
+    lens = [300, 2500, 1700, 3600, 17, 0, 900, 2049, 3072, 1]
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * len(lens), lens, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=8, kv_heads=2, headroom_pages=16)
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 78, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0, tuning=dict(round_items=64, short_list_chunks=short_list_chunks))
+    gb.preload_gpu(gpu, wl, 78, 1.0)
+    q, k, v = harness.step_inputs(78, 0, cfg, 1.0)
+    want = np.zeros((len(lens), 8, 128), dtype=np.float32)
+    for b in range(len(lens)):
+        if lens[b] > 0:
+            kb, vb = ora.gather_kv(0, b)
+            want[b] = attention.attend(bf16.to_f64(q[0][b]), bf16.to_f64(kb), bf16.to_f64(vb), 128 ** -0.5)
+    gpu.scheduled = True
+    gpu.max_len_hint = max(lens)
+    check_attention(gpu.decode_attn(0, q[0], 128 ** -0.5), want)
+    check_attention(gpu.decode_attn(0, q[0], 128 ** -0.5, out_dtype=torch.bfloat16), want)
+    assert gpu.status() == 0
+    ws = gpu.ctx.attn_ws.view(torch.int32).cpu().numpy()
+    base = len(lens) * 8 * 128 * 130
+    total = int(ws[base])
+    assert total > 0                                                     # the launch was scheduled
+    used_of = ws[base + 4 + 4 * len(lens) * 128: base + 4 + 4 * len(lens) * 128 + len(lens)]
+    chunks = [(n + 255) // 256 for n in lens]
+    fits = [per for per in range(1, 129) if all(int(used_of[b]) == -(-c // per) for b, c in enumerate(chunks))]
+    assert fits, (list(used_of), chunks)
+    if short_list_chunks:     # clamped to half .. twice the launch's chunks per block (6, less where the fill rule shrank it)
+        assert any(min(max(short_list_chunks, max(c // 2, 1)), 2 * c) in fits for c in range(1, 7)), (fits, list(used_of))
+    assert total == sum(max(int(u), 1) for u in used_of)
+
+
 @pytest.mark.parametrize("page_size", [16, 1])
 @pytest.mark.parametrize("waves", [4, 6, 8, 12])
 def test_every_block_width_of_the_attention_kernel(gb, waves, page_size):
