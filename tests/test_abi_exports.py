@@ -62,3 +62,13 @@ def test_host_side_argument_checks_need_no_gpu():
         assert lib.tim_ctx_set_tuning(h, ctypes.byref(t3)) == tim.ERR_INVALID_ARG, field
     assert lib.tim_ctx_get_tuning(h, ctypes.byref(t3)) == tim.OK and t3.chunks_per_block == 3     # refused: unchanged
     assert lib.tim_ctx_destroy(h) == tim.OK
+
+
+def test_bench_refuses_more_than_one_gpu_before_touching_any():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
