@@ -28,6 +28,10 @@
  *     own setting, Sec. 3.1; see "Page size 1" below).  Other values are rejected with
  *     TIM_ERR_INVALID_ARG.  One pool layout (below); the rotary pairing is a field of tim_config.
  *   - bf16 is the upper half of an IEEE binary32, round-to-nearest-even.
+ *   - Alignment: device pointers to K/V rows, queries and outputs (the pools, q, out, k_new,
+ *     v_new, k_rows, v_rows, q_ext, out_ext, attn_ws) must be 16-byte aligned, int32 and
+ *     uint32 arrays 4-byte aligned; a pointer that is not is refused with
+ *     TIM_ERR_INVALID_ARG before anything is launched.
  *
  * Data layout
  *   K and V pools: bf16 [layers][num_pages][kv_heads][page_size][head_dim],

@@ -1075,7 +1075,8 @@ void tim_noalloc_scratch_init() {
 static int at_decode(tim_ctx *ctx, int32_t layer, const void *q, void *out, float sm_scale, int32_t out_dtype,
                      int32_t max_seq_len, tim_stream stream, bool masked, const void *k_new = nullptr,
                      const void *v_new = nullptr, bool own_scratch = false) {
-  if (!ctx || !ctx->bound || !q || !out || layer < 0 || layer >= ctx->cfg.layers || (!own_scratch && !ctx->st.attn_ws) ||
+  if (!ctx || !ctx->bound || !tim_rows_ok(q) || !tim_rows_ok(out) || !tim_aligned(k_new, 16) || !tim_aligned(v_new, 16) ||
+      layer < 0 || layer >= ctx->cfg.layers || (!own_scratch && !ctx->st.attn_ws) ||
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16) || max_seq_len < 0 || (masked && !ctx->st.keep_mask) ||
       (ctx->cfg.page_size == 1 && ctx->attn_impl != 1 && !masked))  // page size 1 exists for the matrix-core kernels only
     return TIM_ERR_INVALID_ARG;

@@ -72,9 +72,11 @@ extern "C" int tim_ctx_destroy(tim_ctx *ctx) {
 
 extern "C" int tim_bind(tim_ctx *ctx, const tim_state *s) {
   if (!ctx || !s) return TIM_ERR_INVALID_ARG;
-  if (!s->k_pool || !s->v_pool || !s->page_table || !s->seq_len || !s->free_stack || !s->free_top || !s->status ||
-      !s->node_tok_begin || !s->node_sub_begin || !s->node_sub_end || !s->node_tok_end || !s->node_list_order ||
-      !s->n_nodes || !s->lists_done)
+  if (!tim_rows_ok(s->k_pool) || !tim_rows_ok(s->v_pool) || !tim_ints_ok(s->page_table) || !tim_ints_ok(s->seq_len) ||
+      !tim_ints_ok(s->free_stack) || !tim_ints_ok(s->free_top) || !tim_ints_ok(s->status) || !tim_ints_ok(s->node_tok_begin) ||
+      !tim_ints_ok(s->node_sub_begin) || !tim_ints_ok(s->node_sub_end) || !tim_ints_ok(s->node_tok_end) ||
+      !tim_ints_ok(s->node_list_order) || !tim_ints_ok(s->n_nodes) || !tim_ints_ok(s->lists_done) ||
+      !tim_aligned(s->attn_ws, 16) || !tim_aligned(s->keep_mask, 4))
     return TIM_ERR_INVALID_ARG;
   // the workspace is optional (tim_decode_attn_noalloc needs none); if given it must be large enough
   if (s->attn_ws && s->attn_ws_bytes < tim_attn_ws_bytes(&ctx->cfg)) return TIM_ERR_INVALID_ARG;

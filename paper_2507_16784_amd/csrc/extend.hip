@@ -411,7 +411,7 @@ extern "C" int tim_extend_attn(tim_ctx *ctx, int32_t layer, const tim_plan *plan
       ctx->cfg.page_size != TIM_PS ||  // the extend kernel reads 16-token pages only
       (out_dtype != TIM_OUT_F32 && out_dtype != TIM_OUT_BF16))
     return TIM_ERR_INVALID_ARG;
-  if (n_ext_total > 0 && (!q_ext || !out_ext)) return TIM_ERR_INVALID_ARG;  // (with no rows the kernel only checks the plan)
+  if (n_ext_total > 0 && (!tim_rows_ok(q_ext) || !tim_rows_ok(out_ext))) return TIM_ERR_INVALID_ARG;  // (with no rows the kernel only checks the plan)
   // every sequence adds at most one partly filled tile
   const int tiles = (n_ext_total + EX_TILE_TOKENS - 1) / EX_TILE_TOKENS + plan->n_seqs;
   dim3 grid(ctx->cfg.kv_heads, tiles);

@@ -348,13 +348,14 @@ tim_prune_mask_kernel(tim_config cfg, tim_state st, tim_plan pl, const int32_t *
 }
 
 static int plan_ok(const tim_ctx *ctx, const tim_plan *p) {
-  return ctx && ctx->bound && p && p->seq_ids && p->cover && p->rank && p->kept_idx && p->new_pos && p->delta &&
-         p->src_slot && p->dst_slot && p->new_table && p->hdr && p->totals;
+  return ctx && ctx->bound && p && tim_ints_ok(p->seq_ids) && tim_ints_ok(p->cover) && tim_ints_ok(p->rank) &&
+         tim_ints_ok(p->kept_idx) && tim_ints_ok(p->new_pos) && tim_ints_ok(p->delta) && tim_ints_ok(p->src_slot) &&
+         tim_ints_ok(p->dst_slot) && tim_ints_ok(p->new_table) && tim_ints_ok(p->hdr) && tim_ints_ok(p->totals);
 }
 
 extern "C" int tim_prune_plan(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t threshold, tim_plan *plan,
                               tim_stream stream) {
-  if (!plan_ok(ctx, plan) || !seq_ids || n_seqs <= 0 || n_seqs > plan->max_seqs || n_seqs > ctx->cfg.max_batch ||
+  if (!plan_ok(ctx, plan) || !tim_ints_ok(seq_ids) || n_seqs <= 0 || n_seqs > plan->max_seqs || n_seqs > ctx->cfg.max_batch ||
       threshold < 0)
     return TIM_ERR_INVALID_ARG;
   plan->n_seqs = n_seqs;
@@ -383,7 +384,8 @@ extern "C" int tim_plan_commit(tim_ctx *ctx, const tim_plan *plan, tim_stream st
 
 extern "C" int tim_prune_mask(tim_ctx *ctx, const int32_t *seq_ids, int32_t n_seqs, int32_t threshold, tim_plan *plan,
                               tim_stream stream) {
-  if (!ctx || !ctx->bound || !ctx->st.keep_mask || !plan || !plan->cover || !plan->new_pos || !seq_ids || n_seqs <= 0 ||
+  if (!ctx || !ctx->bound || !ctx->st.keep_mask || !plan || !tim_ints_ok(plan->cover) || !tim_ints_ok(plan->new_pos) ||
+      !tim_ints_ok(seq_ids) || n_seqs <= 0 ||
       n_seqs > plan->max_seqs || n_seqs > ctx->cfg.max_batch || threshold < 0)
     return TIM_ERR_INVALID_ARG;
   hipLaunchKernelGGL(tim_prune_mask_kernel, dim3(n_seqs), dim3(PLAN_THREADS), 0, tim_hs(stream), ctx->cfg, ctx->st, *plan,

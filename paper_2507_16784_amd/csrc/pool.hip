@@ -281,7 +281,7 @@ extern "C" int tim_pool_reset(tim_ctx *ctx, tim_stream stream) {
 }
 
 extern "C" int tim_tree_mark(tim_ctx *ctx, const int32_t *ops, int32_t n_ops, tim_stream stream) {
-  if (!ctx || !ctx->bound || n_ops < 0 || (n_ops > 0 && !ops)) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || n_ops < 0 || (n_ops > 0 && !tim_ints_ok(ops))) return TIM_ERR_INVALID_ARG;
   if (n_ops == 0) return TIM_OK;
   const int threads = 64;
   const int blocks = (ctx->cfg.max_batch + threads - 1) / threads;
@@ -301,7 +301,7 @@ extern "C" int tim_seq_advance(tim_ctx *ctx, tim_stream stream) {
 }
 
 extern "C" int tim_seq_extend(tim_ctx *ctx, const int32_t *counts, tim_stream stream) {
-  if (!ctx || !ctx->bound || !counts) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || !tim_ints_ok(counts)) return TIM_ERR_INVALID_ARG;
   ctx->sched_valid = false;  // lengths change: an attention schedule no longer holds
   int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
@@ -312,9 +312,9 @@ extern "C" int tim_seq_extend(tim_ctx *ctx, const int32_t *counts, tim_stream st
 
 extern "C" int tim_kv_write(tim_ctx *ctx, int32_t layer, const int32_t *row_off, int32_t n_rows, const void *k_rows,
                             const void *v_rows, tim_stream stream) {
-  if (!ctx || !ctx->bound || !row_off || n_rows < 0 || layer < 0 || layer >= ctx->cfg.layers) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || !tim_ints_ok(row_off) || n_rows < 0 || layer < 0 || layer >= ctx->cfg.layers) return TIM_ERR_INVALID_ARG;
   if (n_rows == 0) return TIM_OK;
-  if (!k_rows || !v_rows) return TIM_ERR_INVALID_ARG;
+  if (!tim_rows_ok(k_rows) || !tim_rows_ok(v_rows)) return TIM_ERR_INVALID_ARG;
   const int64_t total = 2 * (int64_t)n_rows * ctx->cfg.kv_heads * 16;
   const int threads = 256;
   hipLaunchKernelGGL(tim_write_rows_kernel, dim3((unsigned)((total + threads - 1) / threads)), dim3(threads), 0,
@@ -325,7 +325,7 @@ extern "C" int tim_kv_write(tim_ctx *ctx, int32_t layer, const int32_t *row_off,
 }
 
 extern "C" int tim_kv_append(tim_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, tim_stream stream) {
-  if (!ctx || !ctx->bound || !k_new || !v_new || layer < 0 || layer >= ctx->cfg.layers) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || !tim_rows_ok(k_new) || !tim_rows_ok(v_new) || layer < 0 || layer >= ctx->cfg.layers) return TIM_ERR_INVALID_ARG;
   const int total = 2 * ctx->cfg.max_batch * ctx->cfg.kv_heads * 16;
   const int threads = 256;
   hipLaunchKernelGGL(tim_append_kernel, dim3((total + threads - 1) / threads), dim3(threads), 0, tim_hs(stream),
@@ -336,7 +336,7 @@ extern "C" int tim_kv_append(tim_ctx *ctx, int32_t layer, const void *k_new, con
 }
 
 extern "C" int tim_pool_stats(tim_ctx *ctx, int32_t *out, int32_t *scratch, tim_stream stream) {
-  if (!ctx || !ctx->bound || !out) return TIM_ERR_INVALID_ARG;
+  if (!ctx || !ctx->bound || !tim_ints_ok(out) || !tim_aligned(scratch, 4)) return TIM_ERR_INVALID_ARG;
   hipLaunchKernelGGL(tim_stats_clear_kernel, dim3(64), dim3(256), 0, tim_hs(stream), ctx->cfg, out, scratch);
   TIM_LAUNCH_CHECK();
   hipLaunchKernelGGL(tim_stats_kernel, dim3(64), dim3(256), 0, tim_hs(stream), ctx->cfg, ctx->st, out, scratch);

@@ -48,6 +48,12 @@ void tim_noalloc_scratch_init();
 
 static inline hipStream_t tim_hs(tim_stream s) { return reinterpret_cast<hipStream_t>(s); }
 
+// The kernels move K/V rows, queries and outputs in 16-byte pieces and index int32 arrays as such; a
+// pointer that is not aligned for that is refused on the host, never handed to a kernel.
+static inline bool tim_aligned(const void *p, uintptr_t bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; }
+static inline bool tim_rows_ok(const void *p) { return p != nullptr && tim_aligned(p, 16); }
+static inline bool tim_ints_ok(const void *p) { return p != nullptr && tim_aligned(p, 4); }
+
 // words per sequence of the visibility mask: one bit per logical token
 __host__ __device__ __forceinline__ int tim_mask_words(const tim_config &cfg) {
   return (cfg.max_pages_per_seq * cfg.page_size + 31) / 32;

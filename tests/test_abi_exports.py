@@ -61,6 +61,26 @@ def test_host_side_argument_checks_need_no_gpu():
         setattr(t3, field, bad_value)
         assert lib.tim_ctx_set_tuning(h, ctypes.byref(t3)) == tim.ERR_INVALID_ARG, field
     assert lib.tim_ctx_get_tuning(h, ctypes.byref(t3)) == tim.OK and t3.chunks_per_block == 3     # refused: unchanged
+    # alignment is checked on the host: made-up addresses, nothing is launched and no GPU is touched
+    st = tim.tim_state()
+    for name, _ in tim.tim_state._fields_:
+        if name != "attn_ws_bytes":
+            setattr(st, name, 0x10000)
+    st.attn_ws_bytes = lib.tim_attn_ws_bytes(ctypes.byref(ok))
+    assert lib.tim_bind(h, ctypes.byref(st)) == tim.OK
+    for name, off in (("k_pool", 8), ("v_pool", 2), ("attn_ws", 4), ("page_table", 2), ("seq_len", 1), ("keep_mask", 2)):
+        st2 = tim.tim_state.from_buffer_copy(st)
+        setattr(st2, name, 0x10000 + off)
+        assert lib.tim_bind(h, ctypes.byref(st2)) == tim.ERR_INVALID_ARG, name
+    vp = ctypes.c_void_p
+    for q_addr, out_addr in ((0x20008, 0x30000), (0x20000, 0x30004)):
+        assert lib.tim_decode_attn(h, 0, vp(q_addr), vp(out_addr), ctypes.c_float(1.0), 0, 0, None) == tim.ERR_INVALID_ARG
+        assert lib.tim_decode_attn_noalloc(h, 0, vp(q_addr), vp(out_addr), ctypes.c_float(1.0), 0, 0, None) == tim.ERR_INVALID_ARG
+    assert lib.tim_decode_attn_append(h, 0, vp(0x20000), vp(0x40002), vp(0x50000), vp(0x30000), ctypes.c_float(1.0), 0, 0,
+                                      None) == tim.ERR_INVALID_ARG
+    assert lib.tim_kv_append(h, 0, vp(0x40000), vp(0x50008), None) == tim.ERR_INVALID_ARG
+    assert lib.tim_tree_mark(h, vp(0x60002), 1, None) == tim.ERR_INVALID_ARG
+    assert lib.tim_seq_extend(h, vp(0x60001), None) == tim.ERR_INVALID_ARG
     assert lib.tim_ctx_destroy(h) == tim.OK
 
 
