@@ -28,21 +28,24 @@ HBM_PEAK_GBPS = 8000.0
 KV_BYTES_PER_TOKEN_LAYER = 4096          # K + V rows of 8 KV heads x 128 dims, bf16
 
 
-TRAFFIC_FILE = "profiles/attn_mfma_config3_hbm_traffic.txt"
+# (batch, steps, seed) -> the committed counter summary measured on exactly that workload
+TRAFFIC_FILES = {(64, 256, 1000): "profiles/attn_mfma_config3_hbm_traffic.txt",
+                 (64, 20, 1000): "profiles/attn_mfma_config3_first20_hbm_traffic.txt"}
 
 
 def stored_traffic(batch, steps, seed):
     """HBM bytes per attention launch from the committed rocprofv3 counter runs (two separate --pmc runs of
-    this same command; counters cannot be read from inside the run).  They were taken on the default
-    workload, so any other workload reports null.  Returns (bytes, label of where the figure comes from)."""
-    path = os.path.join(ROOT, TRAFFIC_FILE)
-    if (batch, steps, seed) != (64, 256, 1000) or not os.path.exists(path):
+    this same command; counters cannot be read from inside the run).  They exist for the default window and
+    for its first 20 steps; any other workload reports null.  Returns (bytes, label of where the figure comes from)."""
+    rel = TRAFFIC_FILES.get((batch, steps, seed))
+    path = os.path.join(ROOT, rel) if rel else None
+    if not path or not os.path.exists(path):
         return None, None
     for line in open(path):
         if line.startswith("attn_partial_mfma_traffic_bytes_per_launch"):
-            return float(line.split("=")[1]), (TRAFFIC_FILE + ": rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
-                                               "(batch 64, 256 steps, seed 1000), stored with the kernel they measured; "
-                                               "not re-measured in this run")
+            return float(line.split("=")[1]), (rel + ": rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
+                                               f"(batch {batch}, {steps} steps, seed {seed}), stored with the kernel they "
+                                               "measured; not re-measured in this run")
     return None, None
 
 
