@@ -340,7 +340,8 @@ int tim_decode_attn(tim_ctx *ctx, int32_t layer, const void *q, void *out, float
  * flush) spends a good part of a launch on blocks that find nothing to do.  max_seq_len as
  * in tim_decode_attn; the calls that follow use this call's bound and ignore their own.
  * When the bound's whole grid fits the chip at once, or the batch is one sequence, there is
- * nothing to reorder: the call then does nothing and the calls that follow run unscheduled.
+ * nothing to reorder: the call then does nothing and the calls that follow run unscheduled;
+ * so do batches of more than 4096 sequences (what the call's kernel holds in LDS).
  * The schedule lapses at the next tim_seq_advance, tim_seq_extend, tim_plan_commit,
  * tim_pool_reset or tim_bind.  A caller that changes tim_state.seq_len by other means must
  * call this again: a stale schedule is detected per block and reported as

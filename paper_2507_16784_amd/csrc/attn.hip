@@ -29,6 +29,7 @@
 #define AT_BLOCKS_PER_CU 3  // of the matrix-core kernel: what its registers allow
 #define AT_GRADE_MIN_ROUNDS 3
 #define AT_MAX_CPB 64  // tim_tuning.chunks_per_block is at most this
+#define AT_SCHED_STAGE 4096  // largest batch that is scheduled: the schedule kernel keeps four words per sequence in LDS
 #define AT_NEG_BIG (-1.0e30f)
 
 __device__ __forceinline__ float at_bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -871,69 +872,115 @@ tim_attn_schedule_kernel(tim_config cfg, tim_state st, int32_t *__restrict__ sch
   // length take the largest (fewer partial results: 64 x 2,500 tokens, 102 us per launch whole against 104 in
   // halves), unequal ones the smallest (the even spread the model assumes needs many small blocks: 5.76-5.79
   // TB/s at 3 or 4 chunks against 5.53 at 6 in the measurement above, all three tied at 24 in the model).
+  //
+  // One block; every pass reads the lengths and slot counts from LDS, and the two passes that compare every
+  // sequence with every other one are spread over all threads (P threads per sequence, joined by LDS atomics):
+  // the kernel runs once per decode step in front of the step's attention launches, alone on the chip, so its
+  // length is latency, not work.  (As first written - one thread per sequence, every pass re-reading the lengths
+  // from global memory, one atomic per sequence and candidate size - it took 39 us for 64 sequences.)
   __shared__ int s_items[2 * AT_MAX_CPB + 1];
-  __shared__ int s_per, s_cmin, s_cmax;
+  __shared__ int s_per, s_cmin, s_cmax, s_work_total, s_items_total;
+  __shared__ unsigned long long s_best;
+  __shared__ int s_len[AT_SCHED_STAGE], s_used[AT_SCHED_STAGE], s_work_before[AT_SCHED_STAGE], s_before[AT_SCHED_STAGE];
+  const int B = cfg.max_batch, T = blockDim.x, tid = threadIdx.x;  // B <= AT_SCHED_STAGE (checked by the host)
+  int P = 1;  // threads per sequence in the all-pairs passes: a power of two, at most T / B
+  while (2 * P * B <= T) P *= 2;
+  const int part = tid % P, seqs_per_pass = T / P;
   const int per_lo = max(cpb / 2, 1), per_hi = 2 * cpb, cu_items = max(round_chunks / cpb / AT_BLOCKS_PER_CU, 1);
-  for (int i = threadIdx.x; i <= 2 * AT_MAX_CPB; i += blockDim.x) s_items[i] = 0;
-  if (threadIdx.x == 0) {
+  for (int i = tid; i <= 2 * AT_MAX_CPB; i += T) s_items[i] = 0;
+  if (tid == 0) {
     s_cmin = INT32_MAX;
-    s_cmax = 0;
+    s_cmax = s_work_total = s_items_total = 0;
+    s_best = ~0ull;
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
-    const int c = at_chunks_of(st.seq_len[b]);
-    if (c > 0) {
-      atomicMin(&s_cmin, c);
-      atomicMax(&s_cmax, c);
-    }
-    for (int per = per_lo; per <= per_hi; ++per) atomicAdd(&s_items[per], max(min(slots, (c + per - 1) / per), 1));
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int best = cpb;
-    int64_t best_cost = INT64_MAX;
-    const bool equal_lengths = s_cmin >= s_cmax;
-    for (int per = per_lo; per <= per_hi; ++per) {
-      const int64_t cost = (int64_t)((s_items[per] + cu_items - 1) / cu_items) * per;
-      if (cost < best_cost || (cost == best_cost && equal_lengths)) {
-        best_cost = cost;
-        best = per;
+  {
+    int cmin = INT32_MAX, cmax = 0, csum = 0;  // (chunks of the whole batch: at most num_pages / 16)
+    for (int b = tid; b < B; b += T) {
+      const int n = st.seq_len[b], c = at_chunks_of(n);
+      s_len[b] = n;
+      s_work_before[b] = s_before[b] = 0;
+      csum += c;
+      if (c > 0) {
+        cmin = min(cmin, c);
+        cmax = max(cmax, c);
       }
     }
-    s_per = short_per > 0 ? min(max(short_per, per_lo), per_hi) : best;
+    if (cmax > 0) {
+      atomicMin(&s_cmin, cmin);
+      atomicMax(&s_cmax, cmax);
+      atomicAdd(&s_work_total, csum);
+    }
   }
   __syncthreads();
-  const int per_short = s_per;
-  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
-    const int n = st.seq_len[b], c = at_chunks_of(n);
-    int64_t work_before = 0, work_total = 0;
-    for (int o = 0; o < cfg.max_batch; ++o) {
-      const int no = st.seq_len[o], co = at_chunks_of(no);
-      work_total += co;
-      if (no > n || (no == n && o < b)) work_before += co;
+  // blocks per candidate size: thread (group, candidate) sums over every 'groups'-th sequence
+  {
+    const int lanes = 16, groups = T / lanes, group = tid / lanes;
+    for (int per = per_lo + tid % lanes; per <= per_hi; per += lanes) {
+      int sum = 0;
+#pragma unroll 4
+      for (int b = group; b < B; b += groups) sum += max(min(slots, (at_chunks_of(s_len[b]) + per - 1) / per), 1);
+      atomicAdd(&s_items[per], sum);
     }
-    int per = per_short;
-    const int64_t to_go = work_total - work_before;
-    if (work_total >= (int64_t)AT_GRADE_MIN_ROUNDS * round_chunks) {
-      per = cpb;
-      if (to_go * 16 > (int64_t)grade_big * round_chunks) per = 2 * cpb;
-      else if (to_go * 16 <= (int64_t)grade_small * round_chunks) per = max(cpb / 2, 1);
-    }
-    used_of[b] = min(slots, (c + per - 1) / per);
   }
-  __syncthreads();  // used_of is complete (global memory written and read by this block only)
-  for (int b = threadIdx.x; b < cfg.max_batch; b += blockDim.x) {
-    const int n = st.seq_len[b], used = used_of[b];
-    int before = 0, total = 0;
-    for (int o = 0; o < cfg.max_batch; ++o) {
-      const int no = st.seq_len[o];
-      const int items = max(used_of[o], 1);
-      total += items;
-      if (no > n || (no == n && o < b)) before += items;
+  // work in front of each sequence in the list's order (longest first, ties: lower index first)
+  for (int b = tid / P; b < B; b += seqs_per_pass) {
+    const int n = s_len[b];
+    int before = 0;
+#pragma unroll 4
+    for (int o = part; o < B; o += P) {
+      const int no = s_len[o];
+      if (no > n || (no == n && o < b)) before += at_chunks_of(no);
     }
-    if (b == 0) sched[0] = total;
-    int4 *items = reinterpret_cast<int4 *>(sched + AT_SCHED_HDR);
-    for (int s2 = 0; s2 < max(used, 1); ++s2) items[before + s2] = make_int4(b, s2, n, used);
+    if (before > 0) atomicAdd(&s_work_before[b], before);
+  }
+  __syncthreads();
+  // the cheapest size: one thread per candidate, joined by a minimum over (cost, tie order, size)
+  for (int per = per_lo + tid; per <= per_hi; per += T) {
+    const unsigned long long cost = (unsigned long long)((s_items[per] + cu_items - 1) / cu_items) * per;
+    const unsigned tie = s_cmin >= s_cmax ? 255u - per : (unsigned)per;  // equal lengths: the largest; else the smallest
+    atomicMin(&s_best, (cost << 16) | (tie << 8) | (unsigned)per);
+  }
+  __syncthreads();
+  if (tid == 0) s_per = short_per > 0 ? min(max(short_per, per_lo), per_hi) : (int)(s_best & 255u);
+  __syncthreads();
+  {
+    const int64_t work_total = s_work_total;
+    int my_items = 0;
+    for (int b = tid; b < B; b += T) {
+      const int c = at_chunks_of(s_len[b]);
+      int per = s_per;
+      const int64_t to_go = work_total - s_work_before[b];
+      if (work_total >= (int64_t)AT_GRADE_MIN_ROUNDS * round_chunks) {
+        per = cpb;
+        if (to_go * 16 > (int64_t)grade_big * round_chunks) per = 2 * cpb;
+        else if (to_go * 16 <= (int64_t)grade_small * round_chunks) per = max(cpb / 2, 1);
+      }
+      const int used = min(slots, (c + per - 1) / per);
+      used_of[b] = used;
+      s_used[b] = used;
+      my_items += max(used, 1);
+    }
+    if (my_items > 0) atomicAdd(&s_items_total, my_items);
+  }
+  __syncthreads();
+  // items in front of each sequence, then its own
+  for (int b = tid / P; b < B; b += seqs_per_pass) {
+    const int n = s_len[b];
+    int before = 0;
+#pragma unroll 4
+    for (int o = part; o < B; o += P) {
+      const int no = s_len[o];
+      if (no > n || (no == n && o < b)) before += max(s_used[o], 1);
+    }
+    if (before > 0) atomicAdd(&s_before[b], before);
+  }
+  __syncthreads();
+  if (tid == 0) sched[0] = s_items_total;
+  int4 *items = reinterpret_cast<int4 *>(sched + AT_SCHED_HDR);
+  for (int b = tid / P; b < B; b += seqs_per_pass) {
+    const int n = s_len[b], used = s_used[b], before = s_before[b];
+    for (int s2 = part; s2 < max(used, 1); s2 += P) items[before + s2] = make_int4(b, s2, n, used);
   }
 }
 
@@ -944,6 +991,7 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
   // and on configuration 4, 117 MB per launch, the list's order paired blocks on CUs worse than the grid's:
   // 29.5 vs 27.0 us per launch), or when there is one sequence: the calls then run unscheduled.
   ctx->sched_valid = false;
+  if (ctx->cfg.max_batch > AT_SCHED_STAGE) return TIM_OK;  // beyond what the schedule kernel holds in LDS
   if (ctx->round_items == 0 &&
       (ctx->cfg.max_batch == 1 ||
        (int64_t)ctx->cfg.max_batch * ctx->cfg.kv_heads * ctx->sched_slots <= (int64_t)AT_BLOCKS_PER_CU * ctx->n_cu))
@@ -957,8 +1005,7 @@ extern "C" int tim_attn_schedule(tim_ctx *ctx, int32_t max_seq_len, tim_stream s
   const int round_chunks =
       (ctx->round_items > 0 ? ctx->round_items : AT_BLOCKS_PER_CU * ctx->n_cu / ctx->cfg.kv_heads) * ctx->sched_cpb;
   int32_t *sched = reinterpret_cast<int32_t *>(ctx->st.attn_ws + at_partials_words(ctx->cfg));
-  int threads = ((ctx->cfg.max_batch + 63) / 64) * 64;
-  if (threads > 1024) threads = 1024;
+  const int threads = ctx->cfg.max_batch <= 64 ? 256 : 1024;
   hipLaunchKernelGGL(tim_attn_schedule_kernel, dim3(1), dim3(threads), 0, tim_hs(stream), ctx->cfg, ctx->st, sched,
                      ctx->sched_slots, ctx->sched_cpb, ctx->grade_big, ctx->grade_small, round_chunks > 0 ? round_chunks : 1,
                      ctx->short_per);
