@@ -155,7 +155,7 @@ def check_kv(ora, gpu, drift_ok=False, oracle_is_ahead=False):
 
 
 def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_check_every=1, fused=False,
-           scheduled=False, tuning=None):
+           scheduled=False, tuning=None, allow_errors=False):
     ora = OracleRuntime(cfg, threshold)
     harness.preload_oracle(ora, wl, seed, kv_scale)
     gpu = gb.GpuRuntime(cfg, threshold, tuning=tuning)
@@ -180,13 +180,19 @@ def replay(gb, wl, cfg, threshold, seed, kv_scale, sm_scale, attend_every=1, kv_
                                 on_event=lambda s, ev: events.append(ev))
         def after_commit(_step, _plan):
             views.append(gpu.plan_view())
-            if check_now:                       # right after the commit, before the next token lands
+            if check_now and events[len(views) - 1].ok:   # right after the commit, before the next token lands
                 check_event_kv(ora, gpu, events[len(views) - 1], before)
                 check_kv(ora, gpu, drift_ok=n_events > 0, oracle_is_ahead=True)   # and the oracle's own lineage
 
         got = harness.run_step(gpu, wl, step, seed, kv_scale, sm_scale, attend=do_att, before_event=snapshot,
                                on_event=after_commit)
-        assert gpu.status() == ora.status == 0
+        assert gpu.status() == ora.status
+        if ora.status != 0:
+            # a flush that found too few free pages (or a table too short for the step): it must have left both
+            # sides untouched and in the same state, with the same sticky error; nothing further is defined
+            assert allow_errors, ora.status
+            assert all(view.ok == ev.ok for ev, view in zip(events, views))
+            return ora, gpu
         for ev, view in zip(events, views):
             check_plan(ev, view)
             n_events += 1
@@ -242,7 +248,7 @@ def test_config4_prune_heavy_recycling(gb):
     assert ora.seq_len.max() < p0
 
 
-@pytest.mark.parametrize("case", range(10))
+@pytest.mark.parametrize("case", list(range(24)) + [84, 129, 144])   # the last three draw a flush that runs out of pages
 def test_seeded_shape_sweep(gb, case):
     """Shapes no other test fixes by hand: head counts that are not powers of two, layer counts
     that are not multiples of the compaction kernel's layer group, odd batches, both page sizes,
@@ -268,8 +274,9 @@ def test_seeded_shape_sweep(gb, case):
                               rope_base=float(rng.choice([1.0e4, 1.0e6])), rope_pairing=(case // 2) % 2)
     kv_scale = float(rng.choice([1.0, 128 ** -0.5]))
     sm_scale = float(rng.choice([128 ** -0.5, 0.02, 0.3]))
+    # (a drawn shape may leave a flush too few free pages: both sides must then refuse it alike)
     replay(gb, wl, cfg, threshold, 3000 + case, kv_scale, sm_scale, attend_every=int(rng.randint(1, 4)),
-           fused=bool(rng.randint(2)), scheduled=case % 2 == 1)
+           fused=bool(rng.randint(2)), scheduled=case % 2 == 1, allow_errors=True)
 
 
 @pytest.mark.parametrize("n", [1, 15, 16, 17, 255, 256, 257, 1031])
