@@ -397,6 +397,66 @@ def test_scheduled_attention_on_very_unequal_lengths(gb, page_size):
     assert gpu.status() == 0
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_attention_seeded_launch_shapes(gb, case):
+    """Decode attention on drawn batches (empty, tiny, page-ragged and long sequences side by side), head
+    counts, page sizes and launch shapes - chunks per block, fill, block width, schedule round, block size of
+    short lists, with and without a schedule, a bound that is exact, absent or too small, plain and fused
+    append, fp32 and bf16 output - against the definition evaluated by the oracle: the launch shape changes
+    how the work is cut, never what is computed."""
+    from paper_2507_16784_amd.workload.tree import Trace
+    from oracle import attention
+    rng = np.random.RandomState(7000 + case)
+    batch = int(rng.randint(1, 10))
+    kv_heads = int(rng.choice([1, 2, 3, 8]))
+    page_size = 1 if case % 4 == 3 else 16
+    pick = lambda: int(rng.choice([0, int(rng.randint(1, 40)), int(rng.randint(40, 700)), int(rng.choice([255, 256, 257, 511, 512, 513])),
+                                   int(rng.randint(700, 5000)), int(rng.randint(5000, 12000))],
+                                  p=[0.08, 0.22, 0.3, 0.1, 0.2, 0.1]))
+    lens = [pick() for _ in range(batch)]
+    if max(lens) == 0:
+        lens[0] = 5
+    tr = Trace(max(lens) + 8, [], [], [], [], [], [], [])
+    wl = Workload([tr] * batch, lens, 1, {})
+    cfg = harness.make_config(wl, layers=1, q_heads=4 * kv_heads, kv_heads=kv_heads, headroom_pages=8 * (16 // page_size) + batch,
+                              page_size=page_size, max_pages_per_seq=(max(lens) + 1 + page_size - 1) // page_size + int(rng.randint(0, 3)))
+    tuning = dict(chunks_per_block=int(rng.randint(1, 9)), fill=int(rng.randint(1, 5)),
+                  block_waves=int(rng.choice([0, 0, 4, 6, 8, 12])), round_items=int(rng.choice([0, 2, 4, 64])),
+                  short_list_chunks=int(rng.choice([0, 0, 1, 3, 9, 128])))
+    tuning["grade_small"] = int(rng.choice([0, 8]))
+    ora = OracleRuntime(cfg, 0)
+    harness.preload_oracle(ora, wl, 7100 + case, 1.0)
+    gpu = gb.GpuRuntime(cfg, 0, tuning=tuning)
+    gb.preload_gpu(gpu, wl, 7100 + case, 1.0)
+    gpu.scheduled = bool(rng.randint(2))
+    gpu.fused_append = bool(rng.randint(2))
+    sm_scale = float(rng.choice([128 ** -0.5, 0.05, 0.25]))
+
+    def definition(q_bits):                            # the library defines the output of an empty sequence as zero
+        out = np.zeros((batch, 4 * kv_heads, 128), dtype=np.float32)
+        for b in range(batch):
+            if ora.seq_len[b] > 0:
+                kb, vb = ora.gather_kv(0, b)
+                out[b] = attention.attend(bf16.to_f64(q_bits[b]), bf16.to_f64(kb), bf16.to_f64(vb), sm_scale)
+        return out
+
+    q, k, v = harness.step_inputs(7200 + case, 0, cfg, 1.0)
+    for hint in (max(lens), 0, max(lens) // 3):          # exact bound, none (full tables), too small
+        gpu.max_len_hint = hint
+        gpu._sched_fresh = False
+        want = definition(q[0])
+        check_attention(gpu.decode_attn(0, q[0], sm_scale), want)
+        check_attention(gpu.decode_attn(0, q[0], sm_scale, out_dtype=torch.bfloat16), want)
+    # one decode step through the library's own calls (slot reservation, append or fused append, attention)
+    gpu.max_len_hint = max(lens) + 1
+    harness.run_step(ora, wl, 0, 7300 + case, 1.0, sm_scale, attend=False)
+    got = harness.run_step(gpu, wl, 0, 7300 + case, 1.0, sm_scale)
+    check_attention(got[0], definition(harness.step_inputs(7300 + case, 0, cfg, 1.0)[0][0]))
+    check_state(ora, gpu)
+    check_kv(ora, gpu)
+    assert gpu.status() == ora.status == 0
+
+
 @pytest.mark.parametrize("short_list_chunks", [0, 1, 4, 7, 128])
 def test_block_size_of_a_list_too_short_to_grade(gb, short_list_chunks):
     """tim_attn_schedule on a batch after its flushes (a list of under three rounds of work): one block size for
@@ -714,7 +774,7 @@ def test_extend_attention_long_context_and_scales(gb):
     assert gpu.status() == 0
 
 
-@pytest.mark.parametrize("case", range(6))
+@pytest.mark.parametrize("case", range(16))
 def test_extend_attention_seeded_boundaries(gb, case):
     """Extend attention with the first pruned token and the number of moved tokens placed on, just before
     and just after page, page-pair, wave (8 tokens) and tile (32 tokens) boundaries, for head counts that
