@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+POOL_STAGGER = True                      # --no-pool-stagger: A/B of the V pool's placement (tim.alloc_pools)
 METRIC = "decode steps/s + achieved HBM GB/s for prune+compact+paged GQA decode attn"
 HBM_PEAK_GBPS = 8000.0
 KV_BYTES_PER_TOKEN_LAYER = 4096          # K + V rows of 8 KV heads x 128 dims, bf16
@@ -97,8 +98,7 @@ def build_context(torch, tim, shape, wl, headroom_pages, layers_alloc, seed, pag
     log(f"[bench] pool: {num_pages} pages x {L} layers = {per_layer * L / 1e9:.1f} GB "
         f"(HBM free {free_b / 1e9:.1f} GB of {total_b / 1e9:.1f} GB)")
     shp = (L, num_pages, shape.kv_heads, ps, 128)
-    k_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
-    v_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    k_pool, v_pool = tim.alloc_pools(shp, stagger=POOL_STAGGER)
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
     for l in range(L):
@@ -310,8 +310,7 @@ def horizon_mode(torch, tim, np, configs, args):
     log(f"[bench] pool: {num_pages} pages x {shape.layers} layers = {per_layer * shape.layers / 1e9:.1f} GB")
     shp = (shape.layers, num_pages, shape.kv_heads, args.page_size, 128)
     g = torch.Generator(device="cuda"); g.manual_seed(args.seed)
-    k_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
-    v_pool = torch.empty(shp, dtype=torch.bfloat16, device="cuda")
+    k_pool, v_pool = tim.alloc_pools(shp, stagger=POOL_STAGGER)
     for l in range(shape.layers):
         k_pool[l].normal_(0.0, 1.0, generator=g)
         v_pool[l].normal_(0.0, 1.0, generator=g)
@@ -515,13 +514,16 @@ def main():
                     help="16 (default) or 1, the paper's own page size: flushes then move no rows")
     ap.add_argument("--rope-pairing", default="half-split", choices=["half-split", "interleaved"],
                     help="rotary pairing the compaction re-rotates by (window and flush modes); the configurations use half-split")
+    ap.add_argument("--no-pool-stagger", action="store_true",
+                    help="A/B: allocate the V pool with the K pool's alignment instead of 4 KiB (mod 16 KiB) beyond it")
     ap.add_argument("--tune", default="",
                     help="A/B measurements: fields of tim_tuning to override, e.g. block_waves=6,chunks_per_block=8")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB -> 1 GiB elementwise copy kernel three times (counter calibration)")
     args = ap.parse_args()
-    global SCHEDULE
+    global SCHEDULE, POOL_STAGGER
     SCHEDULE = not args.no_schedule
+    POOL_STAGGER = not args.no_pool_stagger
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no cross-GPU exchange and every box here has one GPU; "
               "run with --gpus 1", file=sys.stderr)

@@ -146,6 +146,32 @@ class Plan:
         self.c = tim_plan(max_seqs=max_seqs, n_seqs=0, **{n: getattr(self, n).data_ptr() for n in _PLAN_PTRS})
 
 
+POOL_STAGGER_BYTES = 4096 + 256   # where the V pool starts relative to the K pool ...
+POOL_STAGGER_PERIOD = 16384       # ... modulo this many bytes
+
+
+def alloc_pools(shape, device="cuda", zero=False, stagger=True):
+    """K and V pools of one context (bf16, `shape` = [layers, num_pages, kv_heads, page_size, 128]).
+
+    The library takes any 16-byte-aligned pair.  This allocator starts the V pool one tile and one row (4096 +
+    256 bytes, modulo 16 KiB) beyond the K pool: the K and V tile of a page - with page size 1 the K and V row of
+    a token - which a wave of the attention kernel requests together, then fall on different memory channels
+    (channels interleave every 256 bytes).  Measured on MI355X, attention over 16-32K-token working memories,
+    same box: 16-token pages 6.64 TB/s against 6.59 with equal alignment (4, 8 or 12 KiB do the same, 2 KiB and
+    16 KiB do not); page size 1 6.52 TB/s against 6.23 (256 bytes alone: 6.51, 512: 6.39, 1 KiB and more: 6.23)."""
+    make = torch.zeros if zero else torch.empty
+    n = 1
+    for d in shape:
+        n *= int(d)
+    k = make(tuple(shape), dtype=torch.bfloat16, device=device)
+    if not stagger:
+        return k, make(tuple(shape), dtype=torch.bfloat16, device=device)
+    buf = make(n + POOL_STAGGER_PERIOD // 2, dtype=torch.bfloat16, device=device)
+    off = (k.data_ptr() + POOL_STAGGER_BYTES - buf.data_ptr()) % POOL_STAGGER_PERIOD
+    assert off % 16 == 0
+    return k, buf[off // 2: off // 2 + n].view(tuple(shape))
+
+
 class Context:
     """One decoding context: owns the torch device buffers of tim_state and the tim_ctx handle."""
 
@@ -159,8 +185,7 @@ class Context:
         i32 = dict(dtype=torch.int32, device=device)
         pool_shape = (layers, num_pages, kv_heads, page_size, head_dim)
         if pools is None:
-            self.k_pool = torch.zeros(pool_shape, dtype=torch.bfloat16, device=device)
-            self.v_pool = torch.zeros(pool_shape, dtype=torch.bfloat16, device=device)
+            self.k_pool, self.v_pool = alloc_pools(pool_shape, device, zero=True)
         else:
             self.k_pool, self.v_pool = pools
             assert tuple(self.k_pool.shape) == pool_shape and tuple(self.v_pool.shape) == pool_shape
