@@ -1033,6 +1033,22 @@ def test_wide_batch_exceeds_one_scan_pass(gb):
     replay(gb, wl, cfg, 0, 11, 1.0, 128 ** -0.5, attend_every=6, kv_check_every=1, fused=True, scheduled=True)
 
 
+def test_batch_beyond_what_the_schedule_kernel_holds(gb):
+    """4,200 sequences: more than tim_attn_schedule keeps in LDS (4,096), so the call leaves the launches
+    unscheduled; slot reservation, one flush of every sequence and attention still agree with the oracle."""
+    nseq, steps = 4200, 4
+    rs = np.random.default_rng(5)
+    p0s = [int(x) for x in rs.integers(1, 40, nseq)]
+    base = [generate(700 + i, 60, SPEC_TINY) for i in range(8)]
+    traces = [base[i % 8] for i in range(nseq)]
+    wl = Workload(traces, p0s, steps, {2: list(range(nseq))})
+    cfg = harness.make_config(wl, layers=1, q_heads=4, kv_heads=1, headroom_pages=9000)
+    ora, gpu = replay(gb, wl, cfg, 0, 12, 1.0, 128 ** -0.5, attend_every=3, kv_check_every=1, fused=True, scheduled=True,
+                      tuning=dict(round_items=4))
+    ws = gpu.ctx.attn_ws.view(torch.int32)
+    assert int(ws[nseq * 4 * 128 * 130].item()) == 0     # the work list was never written: its item count is still zero
+
+
 def test_one_sequence_longer_than_the_slot_cap(gb):
     """40,000 tokens in one sequence: more 256-token chunks than attention slots, so blocks stride."""
     from paper_2507_16784_amd.workload.tree import Trace
