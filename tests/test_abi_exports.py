@@ -92,3 +92,15 @@ def test_bench_refuses_more_than_one_gpu_before_touching_any():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_pool_allocator_places_the_v_pool_one_tile_and_one_row_beyond_the_k_pools_alignment():
+    shape = (2, 5, 2, 16, 128)
+    for _ in range(3):                      # whatever base addresses the allocator hands out
+        k, v = tim.alloc_pools(shape, device="cpu", zero=True)
+        assert tuple(k.shape) == tuple(v.shape) == shape and k.is_contiguous() and v.is_contiguous()
+        assert (v.data_ptr() - k.data_ptr()) % tim.POOL_STAGGER_PERIOD == tim.POOL_STAGGER_BYTES == 4096 + 256
+        assert v.data_ptr() % 16 == 0 and k.data_ptr() % 16 == 0
+        assert float(v.float().abs().sum()) == 0.0
+    k, v = tim.alloc_pools(shape, device="cpu", stagger=False)
+    assert tuple(v.shape) == shape
